@@ -1,0 +1,169 @@
+/*
+ * hbp.h — C ABI of the MI355X (gfx950) packed varlen causal attention library.
+ *
+ * One packed buffer holds many samples of different lengths back to back; every token attends
+ * only inside its own sample (block-diagonal causal mask given by cu_seqlens).  This is where
+ * the attention complexity of a pack, sum_i s_i^2, is spent (paper: Section 1, third
+ * paragraph; Section 3.1, ABR paragraph; Appendix D, layer cost 24Bsh^2 + 4B*sum s_i^2).
+ *
+ * Conventions
+ *  - Plain C.  Every function returns an hbp_status (0 = HBP_OK) and never throws or aborts.
+ *  - The caller owns every buffer.  The library allocates no device memory, never
+ *    synchronises the device and uses only the caller's workspace for scratch.
+ *  - "host" / "device" on a pointer says where the memory must live.
+ *  - Device entry points enqueue work on the caller's HIP stream (a hipStream_t passed as
+ *    void*; NULL = the default stream) and return without waiting.
+ *  - Layouts ("thd"): Q [T,Hq,d_qk], K [T,Hkv,d_qk], V [T,Hkv,d_v], O/dO [T,Hq,d_v],
+ *    dQ like Q, dK like K, dV like V: bf16, innermost dimension contiguous, token and head
+ *    strides in elements (0 = dense).  LSE [Hq,T] fp32 dense.  cu_seqlens int32 [n_samples+1].
+ *  - Query head h reads kv head h / (Hq/Hkv) (contiguous groups).
+ *  - Supported head dims (d_qk, d_v): (64,64), (128,128), (192,128).
+ */
+#ifndef HBP_H
+#define HBP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t hbp_status;
+enum {
+  HBP_OK = 0,
+  HBP_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, bad enum value            */
+  HBP_ERR_SHAPE = 2,       /* Hq % Hkv != 0, stride smaller than the row it must hold    */
+  HBP_ERR_UNSUPPORTED = 3, /* head dims outside the supported set                        */
+  HBP_ERR_CAPACITY = 4,    /* an output array of the planner is too small                */
+  HBP_ERR_WORKSPACE = 5,   /* workspace missing, misaligned or smaller than required     */
+  HBP_ERR_DEVICE = 6       /* the HIP runtime refused the launch (hipGetLastError)       */
+};
+
+/* Static, never-freed description of a status code. */
+const char* hbp_status_string(hbp_status s);
+
+/* One work item of a pack: rows [row_begin,row_end) of the packed buffer, all inside sample
+ * `sample`, being tile number `tile` of that sample (row_begin = cu[sample] + tile*tile_rows). */
+typedef struct {
+  int32_t sample, tile, row_begin, row_end;
+} hbp_tile;
+
+enum { HBP_TILES_QUERY = 0, HBP_TILES_KEY = 1 };
+enum { HBP_FWD = 0, HBP_BWD = 1 };
+
+/*
+ * hbp_pack_plan — host only, integer only, deterministic.
+ *
+ * Packing of ONE pack (paper Section 4.2 step 1 "Packing", Algorithm 2; the paper allows any
+ * packer): walk `lengths` in order, give each sample min(length, space left) tokens, stop when
+ * the pack holds pack_len tokens or the list ends (an under-full pack is legal: no padding
+ * sample is invented).  Then the Attention Balance Sort of Algorithm 7 applied one level down:
+ * cut every sample into tiles of tile_rows rows, give each tile its exact number of causal
+ * (query,key) pairs as cost — kind HBP_TILES_QUERY: pairs whose query is in the tile,
+ * HBP_TILES_KEY: pairs whose key is in the tile — and sort by (cost descending, sample
+ * ascending, tile ascending).  pack_cost is Algorithm 7's a = sum len(x)^2 of the pack.
+ *
+ * All pointers are HOST memory.  Size query: pass cu_seqlens = NULL and/or tiles = NULL (with
+ * tile_cost = NULL); the counts are still written.  Outputs that are non-NULL must have room:
+ * cu_cap >= n_samples+1, tile_cap >= n_tiles, else HBP_ERR_CAPACITY (counts still written).
+ * Errors: HBP_ERR_INVALID_ARG for lengths == NULL with n_lengths > 0, n_lengths < 0,
+ * pack_len <= 0, tile_rows <= 0, bad kind, any length <= 0, NULL count outputs.
+ */
+hbp_status hbp_pack_plan(const int32_t* lengths, int32_t n_lengths, int32_t pack_len,
+                         int32_t tile_rows, int32_t kind,
+                         int32_t* cu_seqlens, int32_t cu_cap, int32_t* n_samples_out,
+                         int32_t* n_consumed_out,
+                         hbp_tile* tiles, int64_t* tile_cost, int32_t tile_cap,
+                         int32_t* n_tiles_out, int64_t* pack_cost_out);
+
+/* Problem description shared by forward and backward. */
+typedef struct {
+  int32_t total_tokens; /* T = cu_seqlens[n_samples]                                   */
+  int32_t n_samples;
+  int32_t n_q_heads, n_kv_heads;
+  int32_t d_qk, d_v;
+  float softmax_scale;  /* <= 0: 1/sqrt(d_qk)                                          */
+  int32_t reserved;     /* must be 0                                                    */
+  /* strides in elements; 0 = dense ([T,H,dim] contiguous).  dQ/dK/dV/dO/O use the o_ and
+   * the q_/k_/v_ strides of the tensor they mirror (dO and O share o_*).               */
+  int64_t q_stride_t, q_stride_h, k_stride_t, k_stride_h;
+  int64_t v_stride_t, v_stride_h, o_stride_t, o_stride_h;
+} hbp_attn_desc;
+
+/* Rows per tile the kernels of this (d_qk, d_v) pair expect from hbp_pack_plan:
+ * which = HBP_FWD: query tiles of the forward; HBP_BWD: key tiles of the backward.
+ * Returns HBP_ERR_UNSUPPORTED for other head dims. */
+hbp_status hbp_tile_rows(int32_t d_qk, int32_t d_v, int32_t which, int32_t* rows_out);
+
+/* Bytes of device workspace a call needs (256-byte aligned base required).
+ * which = HBP_FWD or HBP_BWD.  Forward: a scheduler counter.  Backward: the counter, the
+ * per-row D = rowsum(dO*O) [Hq,T] fp32 and an fp32 dQ accumulator [T,Hq,d_qk]. */
+hbp_status hbp_workspace_bytes(const hbp_attn_desc* desc, int32_t which, size_t* bytes_out);
+
+/* Optional per-workgroup record written by the persistent kernels when `profile` != NULL
+ * (device memory, hbp_profile_capacity() records). ticks are the 100 MHz constant clock. */
+typedef struct {
+  uint32_t hw_id;      /* raw HW_ID register of the workgroup's first wave (CU, SE, ...)  */
+  uint32_t xcc_id;     /* raw XCC_ID register (accelerator die)                           */
+  uint32_t n_items;    /* work items this workgroup processed                             */
+  uint32_t reserved;
+  uint64_t first_tick; /* when the workgroup took its first item                          */
+  uint64_t last_tick;  /* when it finished its last item                                  */
+  uint64_t busy_ticks; /* sum over items of (end - start)                                 */
+} hbp_profile_rec;
+
+/* Number of hbp_profile_rec the caller must provide = workgroups launched by fwd / bwd-main. */
+hbp_status hbp_profile_capacity(const hbp_attn_desc* desc, int32_t which, int32_t* n_records_out);
+
+/*
+ * hbp_varlen_attn_fwd — O and per-row LSE of causal attention inside each sample.
+ *
+ *   S[r,k] = scale * <Q[r,h,:], K[k,kh,:]>  for cu[i] <= k <= r < cu[i+1];  kh = h/(Hq/Hkv)
+ *   LSE[h,r] = ln sum_k exp(S[r,k]);  O[r,h,:] = sum_k exp(S[r,k]-LSE[h,r]) V[k,kh,:]
+ *
+ * (standard scaled-dot-product softmax attention; the paper fixes only that attention is per
+ * sample inside a pack — Section 1, third paragraph.)  bf16 MFMA with fp32 accumulation,
+ * probabilities rounded to bf16 before the PV product, O stored bf16, LSE fp32.
+ *
+ * q,k,v,o,lse,cu_seqlens,q_tiles,workspace,profile: DEVICE.  desc: HOST.
+ * q_tiles: the HBP_TILES_QUERY list of hbp_pack_plan made with hbp_tile_rows(..., HBP_FWD);
+ * items are served longest first by a persistent grid.  Tiles that are malformed (outside
+ * their sample, longer than the tile size) are skipped, never dereferenced.
+ * Rows of O/LSE not covered by any tile are left untouched.  n_q_tiles == 0 or T == 0: no-op.
+ * Errors: INVALID_ARG (null pointers, negative counts, reserved != 0), SHAPE, UNSUPPORTED,
+ * WORKSPACE, DEVICE.  Nothing is launched when an error is returned.
+ */
+hbp_status hbp_varlen_attn_fwd(const hbp_attn_desc* desc, const void* q, const void* k,
+                               const void* v, const int32_t* cu_seqlens,
+                               const hbp_tile* q_tiles, int32_t n_q_tiles,
+                               void* o, float* lse,
+                               void* workspace, size_t workspace_bytes,
+                               hbp_profile_rec* profile_or_null, void* stream);
+
+/*
+ * hbp_varlen_attn_bwd — dQ, dK, dV of L = sum(O * dO) for the attention above.
+ *
+ *   D[r] = sum_x dO[r,h,x] O[r,h,x];  P = exp(S - LSE);  dP[r,k] = <dO[r,h,:], V[k,kh,:]>
+ *   dS = P * (dP - D[r]);  dQ = scale * dS K;  dK = scale * sum_{h in group} dS^T Q;
+ *   dV = sum_{h in group} P^T dO
+ *
+ * Three launches on `stream`: a pre-pass (D, and zeroing of the fp32 dQ accumulator), the
+ * persistent key-tile kernel (dK/dV in registers, dQ by fp32 atomics into the workspace, so
+ * dQ's summation order is not fixed), and a convert pass (dQ accumulator -> bf16).
+ * kv_tiles: the HBP_TILES_KEY list made with hbp_tile_rows(..., HBP_BWD).
+ * o and lse are the forward's outputs.  Every dK/dV row covered by a tile is written; dQ is
+ * written for all T rows.  Same memory placement and error rules as the forward.
+ */
+hbp_status hbp_varlen_attn_bwd(const hbp_attn_desc* desc, const void* q, const void* k,
+                               const void* v, const void* o, const float* lse, const void* d_o,
+                               const int32_t* cu_seqlens,
+                               const hbp_tile* kv_tiles, int32_t n_kv_tiles,
+                               void* dq, void* dk, void* dv,
+                               void* workspace, size_t workspace_bytes,
+                               hbp_profile_rec* profile_or_null, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HBP_H */

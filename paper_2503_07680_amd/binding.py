@@ -1,0 +1,167 @@
+"""ctypes marshalling for the C ABI of ``include/hbp.h``.  No arithmetic of the method lives here.
+
+Device buffers are passed as ``torch`` tensors (``data_ptr()``), or as raw integer addresses.
+If ``libhbp.so`` is missing the binding raises: there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+HBP_FWD, HBP_BWD = 0, 1
+HBP_TILES_QUERY, HBP_TILES_KEY = 0, 1
+
+EXPORTED_SYMBOLS = ["hbp_status_string", "hbp_pack_plan", "hbp_tile_rows", "hbp_workspace_bytes",
+                    "hbp_profile_capacity", "hbp_varlen_attn_fwd", "hbp_varlen_attn_bwd"]
+
+# numpy view of hbp_profile_rec
+PROFILE_DTYPE = np.dtype([("hw_id", "<u4"), ("xcc_id", "<u4"), ("n_items", "<u4"), ("reserved", "<u4"),
+                          ("first_tick", "<u8"), ("last_tick", "<u8"), ("busy_ticks", "<u8")])
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libhbp.so")
+_lib = None
+
+
+class HbpError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = int(status)
+        super().__init__("%s: %s (status %d)" % (where, hbp_status_string(status), status))
+
+
+class AttnDesc(ctypes.Structure):
+    """Mirror of ``hbp_attn_desc``."""
+    _fields_ = [("total_tokens", ctypes.c_int32), ("n_samples", ctypes.c_int32),
+                ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+                ("d_qk", ctypes.c_int32), ("d_v", ctypes.c_int32),
+                ("softmax_scale", ctypes.c_float), ("reserved", ctypes.c_int32),
+                ("q_stride_t", ctypes.c_int64), ("q_stride_h", ctypes.c_int64),
+                ("k_stride_t", ctypes.c_int64), ("k_stride_h", ctypes.c_int64),
+                ("v_stride_t", ctypes.c_int64), ("v_stride_h", ctypes.c_int64),
+                ("o_stride_t", ctypes.c_int64), ("o_stride_h", ctypes.c_int64)]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libhbp.so; raises if it has not been built (no fallback path exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(
+            "%s not found: build it with `python -m paper_2503_07680_amd.build`" % _LIB_PATH)
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i32, i32p, i64p = ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64)
+    descp = ctypes.POINTER(AttnDesc)
+    lib.hbp_status_string.restype = ctypes.c_char_p
+    lib.hbp_status_string.argtypes = [i32]
+    lib.hbp_pack_plan.restype = i32
+    lib.hbp_pack_plan.argtypes = [i32p, i32, i32, i32, i32, i32p, i32, i32p, i32p, vp, i64p, i32, i32p, i64p]
+    lib.hbp_tile_rows.restype = i32
+    lib.hbp_tile_rows.argtypes = [i32, i32, i32, i32p]
+    lib.hbp_workspace_bytes.restype = i32
+    lib.hbp_workspace_bytes.argtypes = [descp, i32, ctypes.POINTER(ctypes.c_size_t)]
+    lib.hbp_profile_capacity.restype = i32
+    lib.hbp_profile_capacity.argtypes = [descp, i32, i32p]
+    lib.hbp_varlen_attn_fwd.restype = i32
+    lib.hbp_varlen_attn_fwd.argtypes = [descp, vp, vp, vp, vp, vp, i32, vp, vp, vp, ctypes.c_size_t, vp, vp]
+    lib.hbp_varlen_attn_bwd.restype = i32
+    lib.hbp_varlen_attn_bwd.argtypes = [descp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp,
+                                        ctypes.c_size_t, vp, vp]
+    _lib = lib
+    return lib
+
+
+def hbp_status_string(status: int) -> str:
+    return load_library().hbp_status_string(int(status)).decode()
+
+
+def _ptr(x) -> Optional[int]:
+    """Device (or host) address of a torch tensor / int / None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return int(x.data_ptr())
+
+
+def _nbytes(x) -> int:
+    return int(x.numel() * x.element_size())
+
+
+def hbp_pack_plan(lengths: Sequence[int], pack_len: int, tile_rows: int, kind: int):
+    """Returns (cu_seqlens int32[n+1], n_consumed, tiles int32[n_tiles,4], tile_cost int64[n_tiles],
+    pack_cost).  Host only."""
+    lib = load_library()
+    L = np.ascontiguousarray(lengths, dtype=np.int32)
+    Lp = L.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)) if L.size else None
+    ns, nc, nt = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+    pc = ctypes.c_int64()
+    st = lib.hbp_pack_plan(Lp, int(L.size), int(pack_len), int(tile_rows), int(kind), None, 0,
+                           ctypes.byref(ns), ctypes.byref(nc), None, None, 0, ctypes.byref(nt),
+                           ctypes.byref(pc))
+    if st != 0:
+        raise HbpError(st, "hbp_pack_plan")
+    cu = np.zeros(ns.value + 1, dtype=np.int32)
+    tiles = np.zeros((nt.value, 4), dtype=np.int32)
+    cost = np.zeros(nt.value, dtype=np.int64)
+    st = lib.hbp_pack_plan(Lp, int(L.size), int(pack_len), int(tile_rows), int(kind),
+                           cu.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), cu.size,
+                           ctypes.byref(ns), ctypes.byref(nc), tiles.ctypes.data,
+                           cost.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), nt.value,
+                           ctypes.byref(nt), ctypes.byref(pc))
+    if st != 0:
+        raise HbpError(st, "hbp_pack_plan")
+    return cu, int(nc.value), tiles, cost, int(pc.value)
+
+
+def hbp_tile_rows(d_qk: int, d_v: int, which: int) -> int:
+    out = ctypes.c_int32()
+    st = load_library().hbp_tile_rows(int(d_qk), int(d_v), int(which), ctypes.byref(out))
+    if st != 0:
+        raise HbpError(st, "hbp_tile_rows")
+    return int(out.value)
+
+
+def hbp_workspace_bytes(desc: AttnDesc, which: int) -> int:
+    out = ctypes.c_size_t()
+    st = load_library().hbp_workspace_bytes(ctypes.byref(desc), int(which), ctypes.byref(out))
+    if st != 0:
+        raise HbpError(st, "hbp_workspace_bytes")
+    return int(out.value)
+
+
+def hbp_profile_capacity(desc: AttnDesc, which: int) -> int:
+    out = ctypes.c_int32()
+    st = load_library().hbp_profile_capacity(ctypes.byref(desc), int(which), ctypes.byref(out))
+    if st != 0:
+        raise HbpError(st, "hbp_profile_capacity")
+    return int(out.value)
+
+
+def hbp_varlen_attn_fwd(desc: AttnDesc, q, k, v, cu_seqlens, q_tiles, n_q_tiles: int, o, lse,
+                        workspace, profile=None, stream: Optional[int] = None) -> None:
+    """Enqueue the forward on ``stream`` (a raw hipStream_t handle, None = default stream)."""
+    st = load_library().hbp_varlen_attn_fwd(
+        ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(cu_seqlens), _ptr(q_tiles), int(n_q_tiles),
+        _ptr(o), _ptr(lse), _ptr(workspace), 0 if workspace is None else _nbytes(workspace),
+        _ptr(profile), stream)
+    if st != 0:
+        raise HbpError(st, "hbp_varlen_attn_fwd")
+
+
+def hbp_varlen_attn_bwd(desc: AttnDesc, q, k, v, o, lse, d_o, cu_seqlens, kv_tiles, n_kv_tiles: int,
+                        dq, dk, dv, workspace, profile=None, stream: Optional[int] = None) -> None:
+    """Enqueue the backward (prepass, key-tile kernel, dQ convert) on ``stream``."""
+    st = load_library().hbp_varlen_attn_bwd(
+        ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(d_o), _ptr(cu_seqlens),
+        _ptr(kv_tiles), int(n_kv_tiles), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(workspace),
+        0 if workspace is None else _nbytes(workspace), _ptr(profile), stream)
+    if st != 0:
+        raise HbpError(st, "hbp_varlen_attn_bwd")

@@ -1,0 +1,216 @@
+// C ABI: argument validation on the host, then kernel launches on the caller's stream.
+#include <cmath>
+#include <cstring>
+
+#include "common.hpp"
+
+namespace {
+
+constexpr int kNumCU = 256;          // MI355X: 8 accelerator dies x 32 compute units
+constexpr size_t kCounterBytes = 256;
+
+bool dims_supported(int d_qk, int d_v) {
+  return (d_qk == 64 && d_v == 64) || (d_qk == 128 && d_v == 128) || (d_qk == 192 && d_v == 128);
+}
+
+int fwd_blocks_per_cu(int d_qk) { return d_qk <= 64 ? 2 : 1; }
+
+struct Strides {
+  int64_t q_st, q_sh, k_st, k_sh, v_st, v_sh, o_st, o_sh;
+};
+
+hbp_status check_desc(const hbp_attn_desc* d, Strides* st) {
+  if (!d) return HBP_ERR_INVALID_ARG;
+  if (d->reserved != 0) return HBP_ERR_INVALID_ARG;
+  if (d->total_tokens < 0 || d->n_samples < 0 || d->n_q_heads <= 0 || d->n_kv_heads <= 0 ||
+      d->d_qk <= 0 || d->d_v <= 0)
+    return HBP_ERR_INVALID_ARG;
+  if (!std::isfinite(d->softmax_scale)) return HBP_ERR_INVALID_ARG;
+  if (d->n_q_heads % d->n_kv_heads) return HBP_ERR_SHAPE;
+  if (!dims_supported(d->d_qk, d->d_v)) return HBP_ERR_UNSUPPORTED;
+  auto fix = [](int64_t s, int64_t dense) { return s == 0 ? dense : s; };
+  st->q_sh = fix(d->q_stride_h, d->d_qk);
+  st->q_st = fix(d->q_stride_t, (int64_t)d->n_q_heads * d->d_qk);
+  st->k_sh = fix(d->k_stride_h, d->d_qk);
+  st->k_st = fix(d->k_stride_t, (int64_t)d->n_kv_heads * d->d_qk);
+  st->v_sh = fix(d->v_stride_h, d->d_v);
+  st->v_st = fix(d->v_stride_t, (int64_t)d->n_kv_heads * d->d_v);
+  st->o_sh = fix(d->o_stride_h, d->d_v);
+  st->o_st = fix(d->o_stride_t, (int64_t)d->n_q_heads * d->d_v);
+  // every stride must hold its row and keep 16-byte vector accesses aligned
+  const int64_t all[8] = {st->q_st, st->q_sh, st->k_st, st->k_sh, st->v_st, st->v_sh, st->o_st, st->o_sh};
+  for (int64_t s : all)
+    if (s <= 0 || (s % 8) != 0) return HBP_ERR_SHAPE;
+  if (st->q_sh < d->d_qk || st->k_sh < d->d_qk || st->v_sh < d->d_v || st->o_sh < d->d_v)
+    return HBP_ERR_SHAPE;
+  if (st->q_st < d->d_qk || st->k_st < d->d_qk || st->v_st < d->d_v || st->o_st < d->d_v)
+    return HBP_ERR_SHAPE;
+  return HBP_OK;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct BwdLayout {
+  size_t d_off, dq_off, total;
+};
+
+BwdLayout bwd_layout(const hbp_attn_desc* d) {
+  BwdLayout l;
+  l.d_off = kCounterBytes;
+  l.dq_off = align_up(l.d_off + (size_t)d->n_q_heads * d->total_tokens * sizeof(float), 256);
+  l.total = align_up(l.dq_off + (size_t)d->total_tokens * d->n_q_heads * d->d_qk * sizeof(float), 256);
+  return l;
+}
+
+float resolve_scale(const hbp_attn_desc* d) {
+  return d->softmax_scale > 0.f ? d->softmax_scale : 1.0f / std::sqrt((float)d->d_qk);
+}
+
+int grid_for(int64_t n_items, int blocks_per_cu) {
+  const int64_t cap = (int64_t)kNumCU * blocks_per_cu;
+  return (int)(n_items < cap ? n_items : cap);
+}
+
+}  // namespace
+
+extern "C" const char* hbp_status_string(hbp_status s) {
+  switch (s) {
+    case HBP_OK: return "ok";
+    case HBP_ERR_INVALID_ARG: return "invalid argument";
+    case HBP_ERR_SHAPE: return "inconsistent shape or stride";
+    case HBP_ERR_UNSUPPORTED: return "unsupported head dimensions";
+    case HBP_ERR_CAPACITY: return "output array too small";
+    case HBP_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case HBP_ERR_DEVICE: return "HIP runtime error at launch";
+    default: return "unknown status";
+  }
+}
+
+extern "C" hbp_status hbp_tile_rows(int32_t d_qk, int32_t d_v, int32_t which, int32_t* rows_out) {
+  if (!rows_out) return HBP_ERR_INVALID_ARG;
+  if (which != HBP_FWD && which != HBP_BWD) return HBP_ERR_INVALID_ARG;
+  if (!dims_supported(d_qk, d_v)) return HBP_ERR_UNSUPPORTED;
+  *rows_out = 128;
+  return HBP_OK;
+}
+
+extern "C" hbp_status hbp_workspace_bytes(const hbp_attn_desc* desc, int32_t which, size_t* bytes_out) {
+  if (!bytes_out) return HBP_ERR_INVALID_ARG;
+  if (which != HBP_FWD && which != HBP_BWD) return HBP_ERR_INVALID_ARG;
+  Strides st;
+  const hbp_status s = check_desc(desc, &st);
+  if (s != HBP_OK) return s;
+  *bytes_out = which == HBP_FWD ? kCounterBytes : bwd_layout(desc).total;
+  return HBP_OK;
+}
+
+extern "C" hbp_status hbp_profile_capacity(const hbp_attn_desc* desc, int32_t which, int32_t* n_records_out) {
+  if (!n_records_out) return HBP_ERR_INVALID_ARG;
+  if (which != HBP_FWD && which != HBP_BWD) return HBP_ERR_INVALID_ARG;
+  Strides st;
+  const hbp_status s = check_desc(desc, &st);
+  if (s != HBP_OK) return s;
+  *n_records_out = kNumCU * (which == HBP_FWD ? fwd_blocks_per_cu(desc->d_qk) : 1);
+  return HBP_OK;
+}
+
+extern "C" hbp_status hbp_varlen_attn_fwd(const hbp_attn_desc* desc, const void* q, const void* k,
+                                          const void* v, const int32_t* cu_seqlens,
+                                          const hbp_tile* q_tiles, int32_t n_q_tiles, void* o,
+                                          float* lse, void* workspace, size_t workspace_bytes,
+                                          hbp_profile_rec* profile, void* stream) {
+  Strides st;
+  const hbp_status s = check_desc(desc, &st);
+  if (s != HBP_OK) return s;
+  if (n_q_tiles < 0) return HBP_ERR_INVALID_ARG;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < kCounterBytes)
+    return HBP_ERR_WORKSPACE;
+  if (desc->total_tokens == 0 || n_q_tiles == 0) return HBP_OK;
+  if (!q || !k || !v || !o || !lse || !cu_seqlens || !q_tiles) return HBP_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return HBP_ERR_INVALID_ARG;
+
+  hbp::FwdParams p;
+  std::memset(&p, 0, sizeof(p));
+  p.q = static_cast<const uint16_t*>(q);
+  p.k = static_cast<const uint16_t*>(k);
+  p.v = static_cast<const uint16_t*>(v);
+  p.o = static_cast<uint16_t*>(o);
+  p.lse = lse;
+  p.cu = cu_seqlens;
+  p.tiles = q_tiles;
+  p.n_tiles = n_q_tiles;
+  p.n_samples = desc->n_samples;
+  p.T = desc->total_tokens;
+  p.Hq = desc->n_q_heads;
+  p.Hkv = desc->n_kv_heads;
+  p.g = desc->n_q_heads / desc->n_kv_heads;
+  p.q_st = st.q_st; p.q_sh = st.q_sh; p.k_st = st.k_st; p.k_sh = st.k_sh;
+  p.v_st = st.v_st; p.v_sh = st.v_sh; p.o_st = st.o_st; p.o_sh = st.o_sh;
+  p.scale_log2 = resolve_scale(desc) * 1.4426950408889634f;
+  p.counter = static_cast<int32_t*>(workspace);
+  p.prof = profile;
+
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  if (hbp::launch_zero_counter(p.counter, hs) != 0) return HBP_ERR_DEVICE;
+  const int grid = grid_for((int64_t)n_q_tiles * p.Hq, fwd_blocks_per_cu(desc->d_qk));
+  if (hbp::launch_fwd(desc->d_qk, desc->d_v, p, grid, hs) != 0) return HBP_ERR_DEVICE;
+  return HBP_OK;
+}
+
+extern "C" hbp_status hbp_varlen_attn_bwd(const hbp_attn_desc* desc, const void* q, const void* k,
+                                          const void* v, const void* o, const float* lse,
+                                          const void* d_o, const int32_t* cu_seqlens,
+                                          const hbp_tile* kv_tiles, int32_t n_kv_tiles, void* dq,
+                                          void* dk, void* dv, void* workspace,
+                                          size_t workspace_bytes, hbp_profile_rec* profile,
+                                          void* stream) {
+  Strides st;
+  const hbp_status s = check_desc(desc, &st);
+  if (s != HBP_OK) return s;
+  if (n_kv_tiles < 0) return HBP_ERR_INVALID_ARG;
+  const BwdLayout lay = bwd_layout(desc);
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < lay.total)
+    return HBP_ERR_WORKSPACE;
+  if (desc->total_tokens == 0) return HBP_OK;
+  if (!q || !k || !v || !o || !lse || !d_o || !cu_seqlens || !dq || !dk || !dv) return HBP_ERR_INVALID_ARG;
+  if (n_kv_tiles > 0 && !kv_tiles) return HBP_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(d_o) ||
+      !aligned16(dq) || !aligned16(dk) || !aligned16(dv))
+    return HBP_ERR_INVALID_ARG;
+
+  hbp::BwdParams p;
+  std::memset(&p, 0, sizeof(p));
+  p.q = static_cast<const uint16_t*>(q);
+  p.k = static_cast<const uint16_t*>(k);
+  p.v = static_cast<const uint16_t*>(v);
+  p.o = static_cast<const uint16_t*>(o);
+  p.d_o = static_cast<const uint16_t*>(d_o);
+  p.lse = lse;
+  p.dq = static_cast<uint16_t*>(dq);
+  p.dk = static_cast<uint16_t*>(dk);
+  p.dv = static_cast<uint16_t*>(dv);
+  char* ws = static_cast<char*>(workspace);
+  p.counter = reinterpret_cast<int32_t*>(ws);
+  p.D = reinterpret_cast<float*>(ws + lay.d_off);
+  p.dq_acc = reinterpret_cast<float*>(ws + lay.dq_off);
+  p.cu = cu_seqlens;
+  p.tiles = kv_tiles;
+  p.n_tiles = n_kv_tiles;
+  p.n_samples = desc->n_samples;
+  p.T = desc->total_tokens;
+  p.Hq = desc->n_q_heads;
+  p.Hkv = desc->n_kv_heads;
+  p.g = desc->n_q_heads / desc->n_kv_heads;
+  p.q_st = st.q_st; p.q_sh = st.q_sh; p.k_st = st.k_st; p.k_sh = st.k_sh;
+  p.v_st = st.v_st; p.v_sh = st.v_sh; p.o_st = st.o_st; p.o_sh = st.o_sh;
+  p.scale = resolve_scale(desc);
+  p.scale_log2 = p.scale * 1.4426950408889634f;
+  p.prof = profile;
+
+  const int grid = grid_for((int64_t)n_kv_tiles * p.Hkv, 1);
+  if (hbp::launch_bwd(desc->d_qk, desc->d_v, p, grid, static_cast<hipStream_t>(stream)) != 0)
+    return HBP_ERR_DEVICE;
+  return HBP_OK;
+}

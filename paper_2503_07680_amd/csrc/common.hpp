@@ -1,0 +1,94 @@
+// Device-side building blocks shared by the gfx950 attention kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "hbp.h"
+
+namespace hbp {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kWave = 64;
+constexpr int kThreads = 256;  // 4 wavefronts per workgroup, one per SIMD
+
+// v_mfma_f32_32x32x16_bf16: D[32x32] += A[32x16] * B[16x32].
+// Lane l supplies A[l%32][8*(l/32)..+7] and B[8*(l/32)..+7][l%32]; it receives
+// D[8*b + 4*(l/32) + v][l%32] in element 4*b + v (b,v in 0..3).
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+union Frag {
+  bf16x8 v;
+  u32x4 u;
+  uint32_t w[4];
+};
+
+// two fp32 -> packed bf16 pair (round to nearest even), low half = a
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  f32x2 f = {a, b};
+  bf16x2 h = __builtin_convertvector(f, bf16x2);
+  return __builtin_bit_cast(uint32_t, h);
+}
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+__device__ __forceinline__ float xor32(float x) { return __shfl_xor(x, 32, 64); }
+
+// Position of contraction index w (0..15) inside a 16-element chunk of a transposed LDS tile.
+// An MFMA whose B operand is taken straight from an accumulator sees, in lane half hh, the
+// eight rows {4hh+v, 8+4hh+v : v=0..3}; storing row w at slot 8*((w%8)/4) + 4*(w/8) + w%4
+// makes those eight rows one contiguous 16-byte read at offset 8*hh.
+__device__ __forceinline__ int tslot(int w) { return (((w & 7) >> 2) << 3) + ((w >> 3) << 2) + (w & 3); }
+
+__device__ __forceinline__ uint32_t hw_id_reg() {
+  // s_getreg_b32 HW_REG_HW_ID (id 4), offset 0, size 32
+  return __builtin_amdgcn_s_getreg((31 << 11) | (0 << 6) | 4);
+}
+__device__ __forceinline__ uint32_t xcc_id_reg() {
+  // s_getreg_b32 HW_REG_XCC_ID (id 20), offset 0, size 32
+  return __builtin_amdgcn_s_getreg((31 << 11) | (0 << 6) | 20);
+}
+
+struct FwdParams {
+  const uint16_t *q, *k, *v;
+  uint16_t* o;
+  float* lse;
+  const int32_t* cu;
+  const hbp_tile* tiles;
+  int32_t n_tiles, n_samples, T, Hq, Hkv, g;
+  int64_t q_st, q_sh, k_st, k_sh, v_st, v_sh, o_st, o_sh;
+  float scale_log2;  // softmax scale * log2(e)
+  int32_t* counter;
+  hbp_profile_rec* prof;
+};
+
+struct BwdParams {
+  const uint16_t *q, *k, *v, *o, *d_o;
+  const float* lse;
+  uint16_t *dq, *dk, *dv;
+  float* D;       // [Hq,T]
+  float* dq_acc;  // [T,Hq,d_qk] fp32
+  const int32_t* cu;
+  const hbp_tile* tiles;
+  int32_t n_tiles, n_samples, T, Hq, Hkv, g;
+  int64_t q_st, q_sh, k_st, k_sh, v_st, v_sh, o_st, o_sh;
+  float scale, scale_log2;
+  int32_t* counter;
+  hbp_profile_rec* prof;
+};
+
+// launchers implemented in the .hip files; return hipError_t as int
+int launch_fwd(int d_qk, int d_v, const FwdParams& p, int grid, hipStream_t s);
+int launch_bwd(int d_qk, int d_v, const BwdParams& p, int grid, hipStream_t s);
+int launch_zero_counter(int32_t* counter, hipStream_t s);
+
+}  // namespace hbp

@@ -1,0 +1,92 @@
+"""Plumbing around the C ABI: torch device buffers for one pack, plan upload, fwd/bwd calls.
+
+Holds no arithmetic: planning happens in ``hbp_pack_plan`` and all attention math in the HIP
+kernels.  Used by the tests, the smoke check and the benchmark.
+"""
+from __future__ import annotations
+
+from typing import Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+class PackedAttention:
+    """One packed buffer: plan on the host, buffers on ``cuda:0``, kernels through the C ABI."""
+
+    def __init__(self, lengths: Sequence[int], pack_len: int, n_q_heads: int, n_kv_heads: int,
+                 d_qk: int, d_v: int, softmax_scale: float = 0.0, device: str = "cuda:0",
+                 with_profile: bool = False):
+        if not torch.cuda.is_available():
+            raise RuntimeError("PackedAttention needs a GPU: there is no CPU fallback")
+        B.load_library()
+        self.device = torch.device(device)
+        self.rows_fwd = B.hbp_tile_rows(d_qk, d_v, B.HBP_FWD)
+        self.rows_bwd = B.hbp_tile_rows(d_qk, d_v, B.HBP_BWD)
+        self.cu, self.n_consumed, self.q_tiles, self.q_cost, self.pack_cost = B.hbp_pack_plan(
+            lengths, pack_len, self.rows_fwd, B.HBP_TILES_QUERY)
+        _, _, self.kv_tiles, self.kv_cost, _ = B.hbp_pack_plan(
+            lengths, pack_len, self.rows_bwd, B.HBP_TILES_KEY)
+        self.T = int(self.cu[-1])
+        self.n_samples = len(self.cu) - 1
+        self.Hq, self.Hkv, self.d_qk, self.d_v = n_q_heads, n_kv_heads, d_qk, d_v
+        self.desc = B.AttnDesc(total_tokens=self.T, n_samples=self.n_samples, n_q_heads=n_q_heads,
+                               n_kv_heads=n_kv_heads, d_qk=d_qk, d_v=d_v,
+                               softmax_scale=float(softmax_scale))
+        dev = self.device
+        self.cu_dev = torch.from_numpy(self.cu).to(dev)
+        self.q_tiles_dev = torch.from_numpy(self.q_tiles).to(dev)
+        self.kv_tiles_dev = torch.from_numpy(self.kv_tiles).to(dev)
+        self.ws_fwd = torch.empty(B.hbp_workspace_bytes(self.desc, B.HBP_FWD), dtype=torch.uint8, device=dev)
+        self.ws_bwd = None
+        self.prof_fwd = self.prof_bwd = None
+        if with_profile:
+            n = B.hbp_profile_capacity(self.desc, B.HBP_FWD)
+            self.prof_fwd = torch.zeros(n * B.PROFILE_DTYPE.itemsize, dtype=torch.uint8, device=dev)
+            n = B.hbp_profile_capacity(self.desc, B.HBP_BWD)
+            self.prof_bwd = torch.zeros(n * B.PROFILE_DTYPE.itemsize, dtype=torch.uint8, device=dev)
+        T = max(self.T, 1)
+        bf = torch.bfloat16
+        self.o = torch.zeros((T, n_q_heads, d_v), dtype=bf, device=dev)
+        self.lse = torch.zeros((n_q_heads, T), dtype=torch.float32, device=dev)
+        self.dq = self.dk = self.dv = None
+
+    # -- inputs -------------------------------------------------------------------------------
+    def to_device_bf16(self, bits: np.ndarray) -> torch.Tensor:
+        """uint16 bf16 bit patterns [T,H,dim] -> bf16 tensor on the device."""
+        t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(self.device)
+        return t.view(torch.bfloat16)
+
+    # -- calls --------------------------------------------------------------------------------
+    def _stream(self) -> int:
+        return int(torch.cuda.current_stream(self.device).cuda_stream)
+
+    def forward(self, q, k, v):
+        B.hbp_varlen_attn_fwd(self.desc, q, k, v, self.cu_dev, self.q_tiles_dev, len(self.q_tiles),
+                              self.o, self.lse, self.ws_fwd, self.prof_fwd, self._stream())
+        return self.o, self.lse
+
+    def alloc_backward(self):
+        if self.ws_bwd is None:
+            dev, bf, T = self.device, torch.bfloat16, max(self.T, 1)
+            self.ws_bwd = torch.empty(B.hbp_workspace_bytes(self.desc, B.HBP_BWD), dtype=torch.uint8, device=dev)
+            self.dq = torch.zeros((T, self.Hq, self.d_qk), dtype=bf, device=dev)
+            self.dk = torch.zeros((T, self.Hkv, self.d_qk), dtype=bf, device=dev)
+            self.dv = torch.zeros((T, self.Hkv, self.d_v), dtype=bf, device=dev)
+
+    def backward(self, q, k, v, d_o):
+        self.alloc_backward()
+        B.hbp_varlen_attn_bwd(self.desc, q, k, v, self.o, self.lse, d_o, self.cu_dev, self.kv_tiles_dev,
+                              len(self.kv_tiles), self.dq, self.dk, self.dv, self.ws_bwd, self.prof_bwd,
+                              self._stream())
+        return self.dq, self.dk, self.dv
+
+    def profile_records(self, which: int) -> np.ndarray:
+        buf = self.prof_fwd if which == B.HBP_FWD else self.prof_bwd
+        return np.frombuffer(buf.cpu().numpy().tobytes(), dtype=B.PROFILE_DTYPE)
+
+
+def bf16_tensor_to_f32_numpy(t: torch.Tensor) -> np.ndarray:
+    return t.detach().float().cpu().numpy()

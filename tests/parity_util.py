@@ -1,0 +1,134 @@
+"""Shared helpers of the GPU parity tests: run the HIP path through the C ABI, run the oracle on
+the same seeded inputs (all of them, or sampled rows/columns/heads), compare to the stated bars."""
+from __future__ import annotations
+
+import numpy as np
+
+import hbp_workloads as wl
+import oracle
+
+# bars (max-abs / mean-abs on O, max-abs on LSE, relative L2 on gradients)
+O_MAX, O_MEAN, LSE_MAX, GRAD_REL = 2e-2, 2e-3, 1e-3, 1e-2
+
+
+def rel_l2(a, ref):
+    return float(np.linalg.norm((a - ref).ravel()) / max(np.linalg.norm(ref.ravel()), 1e-30))
+
+
+class Case:
+    def __init__(self, lengths, pack_len, Hq, Hkv, d, e, seed=0, sigma=1.0, scale=0.0, name="case"):
+        self.lengths, self.pack_len = list(lengths), int(pack_len)
+        self.Hq, self.Hkv, self.d, self.e = Hq, Hkv, d, e
+        self.seed, self.sigma, self.scale, self.name = seed, sigma, scale, name
+        self.g = Hq // Hkv
+
+    @staticmethod
+    def from_workload(w):
+        return Case(w.lengths, w.pack_len, w.n_q_heads, w.n_kv_heads, w.d_qk, w.d_v, w.seed, w.sigma,
+                    0.0, w.name)
+
+    def bits(self, which, T, heads=None):
+        H, dim = {"q": (self.Hq, self.d), "k": (self.Hkv, self.d), "v": (self.Hkv, self.e),
+                  "do": (self.Hq, self.e)}[which]
+        return wl.tensor_bits(self.seed, which, T, H, dim, self.sigma, heads)
+
+
+def run_gpu(case: Case, with_profile=False):
+    """HIP path, all heads, through the C ABI.  Returns the PackedAttention and numpy results."""
+    import torch
+    from paper_2503_07680_amd.runner import PackedAttention
+    pa = PackedAttention(case.lengths, case.pack_len, case.Hq, case.Hkv, case.d, case.e, case.scale,
+                         with_profile=with_profile)
+    T = pa.T
+    dev = {w: pa.to_device_bf16(case.bits(w, T)) for w in ("q", "k", "v", "do")}
+    pa.forward(dev["q"], dev["k"], dev["v"])
+    pa.backward(dev["q"], dev["k"], dev["v"], dev["do"])
+    torch.cuda.synchronize()
+    out = {"o": pa.o.float().cpu().numpy(), "lse": pa.lse.cpu().numpy(),
+           "dq": pa.dq.float().cpu().numpy(), "dk": pa.dk.float().cpu().numpy(),
+           "dv": pa.dv.float().cpu().numpy()}
+    return pa, dev, out
+
+
+def check_plan(case: Case, pa):
+    """cu_seqlens and both worklists: bit-exact against the integer oracle."""
+    for kind, rows, tiles, cost in ((0, pa.rows_fwd, pa.q_tiles, pa.q_cost), (1, pa.rows_bwd, pa.kv_tiles, pa.kv_cost)):
+        ocu, onc, otiles, ocost, opc = oracle.pack_plan(case.lengths, case.pack_len, rows, kind)
+        assert pa.cu.tolist() == ocu and pa.n_consumed == onc and pa.pack_cost == opc
+        assert [tuple(t) for t in tiles.tolist()] == otiles and cost.tolist() == ocost
+
+
+def compare(case: Case, pa, out, q_heads=None, rows=None, cols=None, label=""):
+    """Compare GPU results with the oracle on a head subset (whole kv groups), a row subset for
+    O/LSE/dQ and a column subset for dK/dV.  None = everything."""
+    T = pa.T
+    if q_heads is None:
+        q_heads = list(range(case.Hq))
+    kv_heads = sorted(set(h // case.g for h in q_heads))
+    # the oracle sees a problem restricted to these heads; groups must be whole for dK/dV
+    whole = all(all((kh * case.g + j) in q_heads for j in range(case.g)) for kh in kv_heads)
+    f32 = lambda w, hs: wl.bf16_bits_to_f32(case.bits(w, T, hs))
+    q, do = f32("q", q_heads), f32("do", q_heads)
+    k, v = f32("k", kv_heads), f32("v", kv_heads)
+    if not whole:
+        # heads that share a kv head with unselected heads: run them as MHA on replicated K/V
+        k = np.stack([wl.bf16_bits_to_f32(case.bits("k", T, [h // case.g]))[:, 0] for h in q_heads], axis=1)
+        v = np.stack([wl.bf16_bits_to_f32(case.bits("v", T, [h // case.g]))[:, 0] for h in q_heads], axis=1)
+    scale = case.scale if case.scale > 0 else None
+    cu = np.asarray(pa.cu, dtype=np.int32)
+    rsel = slice(None) if rows is None else np.asarray(rows)
+    O, LSE = oracle.attn_fwd(q, k, v, cu, scale, rows=rows)
+    dQ = oracle.attn_bwd_dq(q, k, v, do, cu, scale, rows=rows)
+    g_o = out["o"][rsel][:, q_heads]
+    g_lse = out["lse"][q_heads][:, rsel]
+    g_dq = out["dq"][rsel][:, q_heads]
+    res = {"o_max": float(np.abs(g_o - O).max()), "o_mean": float(np.abs(g_o - O).mean()),
+           "lse_max": float(np.abs(g_lse - LSE).max()), "dq_rel": rel_l2(g_dq, dQ)}
+    if whole:
+        csel = slice(None) if cols is None else np.asarray(cols)
+        dK, dV = oracle.attn_bwd_dkdv(q, k, v, do, cu, scale, cols=cols)
+        res["dk_rel"] = rel_l2(out["dk"][csel][:, kv_heads], dK)
+        res["dv_rel"] = rel_l2(out["dv"][csel][:, kv_heads], dV)
+    print("[parity %s %s] %s" % (case.name, label, " ".join("%s=%.3e" % kv for kv in res.items())), flush=True)
+    assert np.isfinite(list(res.values())).all(), res
+    assert res["o_max"] <= O_MAX and res["o_mean"] <= O_MEAN, res
+    assert res["lse_max"] <= LSE_MAX, res
+    assert res["dq_rel"] <= GRAD_REL, res
+    if whole:
+        assert res["dk_rel"] <= GRAD_REL and res["dv_rel"] <= GRAD_REL, res
+    return res
+
+
+def check_dv_identity(case: Case, pa, dev, out):
+    """Holds at any size: rows of P sum to one, so sum_k dV[k,kh] over a sample equals the sum of dO
+    over that sample's rows and the group's heads.  Checked on the GPU outputs for every head."""
+    import torch
+    do = dev["do"].float()
+    dv = torch.from_numpy(out["dv"]).to(do.device)
+    worst = 0.0
+    for i in range(pa.n_samples):
+        a, b = int(pa.cu[i]), int(pa.cu[i + 1])
+        want = do[a:b].sum(dim=0).view(case.Hkv, case.g, case.e).sum(dim=1)
+        got = dv[a:b].sum(dim=0)
+        denom = max(float(want.abs().max()), 1.0)
+        # bf16 rounding of each of the (b-a) stored dV rows bounds the error of their sum
+        tol = 2.0 ** -8 * float(dv[a:b].abs().sum(dim=0).max()) / denom + 1e-3
+        err = float((got - want).abs().max()) / denom
+        worst = max(worst, err / tol)
+        assert err <= tol, (i, err, tol)
+    return worst
+
+
+def sampled_rows(cu, n_random, rng, tile=128):
+    """Sample edges, tile edges of the longest sample, and random rows."""
+    cu = np.asarray(cu)
+    rows = set()
+    for i in range(len(cu) - 1):
+        a, b = int(cu[i]), int(cu[i + 1])
+        rows.update([a, b - 1, min(a + 1, b - 1)])
+    i = int(np.argmax(np.diff(cu)))
+    a, b = int(cu[i]), int(cu[i + 1])
+    for t in range(a, b, tile * max(1, (b - a) // tile // 8)):
+        rows.update([t, min(t + tile - 1, b - 1), min(t + 31, b - 1), min(t + 32, b - 1)])
+    rows.update(int(x) for x in rng.integers(0, cu[-1], n_random))
+    return sorted(rows)
