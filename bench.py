@@ -1,0 +1,213 @@
+#!/usr/bin/env python3
+"""Benchmark of the packed varlen causal attention hot path (plan -> forward -> backward) on one MI355X.
+
+One "step" = one forward + one backward over one synthetic pack, inputs resident in HBM.
+Prints ONE JSON line: useful TFLOP/s (only in-sample causal pairs are counted:
+fwd 2(d_qk+d_v), bwd 2(3 d_qk+2 d_v) flop per pair and head), the roofline of the dominant kernel
+(the backward key-tile kernel) timed live with HIP events, the per-CU busy-time spread from the
+kernels' own profile records, and the fp64 oracle timed on the host as a CPU baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA (published)
+
+
+class HipEvents:
+    """hipEvent_t handles through the HIP runtime (timing on the stream the kernels run on)."""
+
+    def __init__(self):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+
+    def create(self) -> int:
+        ev = ctypes.c_void_p()
+        rc = self.hip.hipEventCreate(ctypes.byref(ev))
+        if rc != 0:
+            raise RuntimeError("hipEventCreate failed: %d" % rc)
+        return ev.value
+
+    def record(self, ev: int, stream: int):
+        rc = self.hip.hipEventRecord(ev, stream)
+        if rc != 0:
+            raise RuntimeError("hipEventRecord failed: %d" % rc)
+
+    def sync(self, ev: int):
+        self.hip.hipEventSynchronize(ev)
+
+    def elapsed_ms(self, a: int, b: int) -> float:
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), a, b)
+        if rc != 0:
+            raise RuntimeError("hipEventElapsedTime failed: %d" % rc)
+        return float(ms.value)
+
+
+def busy_spread(rec: np.ndarray):
+    """Per-CU busy time from per-workgroup records -> (max-min)/max, the ABR form, #CUs seen."""
+    hw, xcc = rec["hw_id"], rec["xcc_id"] & 0xF
+    cu_key = (xcc.astype(np.int64) << 16) | (((hw >> 13) & 7).astype(np.int64) << 8) | \
+             (((hw >> 12) & 1).astype(np.int64) << 4) | ((hw >> 8) & 0xF).astype(np.int64)
+    used = rec["n_items"] > 0
+    keys = np.unique(cu_key[used])
+    busy = np.array([rec["busy_ticks"][used & (cu_key == kq)].sum() for kq in keys], dtype=np.float64)
+    if len(busy) == 0:
+        return None
+    span = float(rec["last_tick"][used].max() - rec["first_tick"][used].min())
+    return {"cus_seen": int(len(keys)), "spread": float((busy.max() - busy.min()) / busy.max()),
+            "abr": float((busy.max() - busy).sum() / (busy.max() * len(busy))),
+            "kernel_span_ms": span / 1e5, "max_cu_busy_ms": float(busy.max()) / 1e5,
+            "workgroups": int(used.sum())}
+
+
+def cpu_baseline(w, cu, target_pairs=2.0e7):
+    """Time the fp64 oracle (fwd + dQ + dK/dV) on a bounded sub-pack of the same workload."""
+    import hbp_workloads as wl
+    import oracle
+    g = w.n_q_heads // w.n_kv_heads
+    lens = np.diff(cu)
+    keep = [i for i in range(len(lens)) if lens[i] <= 4096]
+    if keep:
+        sub_lens = [int(lens[i]) for i in keep]
+        starts = [int(cu[i]) for i in keep]
+        what = "%d samples of <=4096 tokens taken whole from the pack" % len(keep)
+    else:
+        sub_lens = [4096 for _ in lens]
+        starts = [int(cu[i]) for i in range(len(lens))]
+        what = "first 4096 tokens of each sample"
+    pairs = sum(s * (s + 1) // 2 for s in sub_lens)
+    n_groups = int(max(1, min(w.n_kv_heads, round(target_pairs / max(pairs * g, 1)))))
+    q_heads = list(range(n_groups * g))
+    kv_heads = list(range(n_groups))
+    T = int(cu[-1])
+    rows = np.concatenate([np.arange(a, a + s) for a, s in zip(starts, sub_lens)])
+    pick = lambda t, hs: wl.bf16_bits_to_f32(wl.workload_tensor_bits(w, t, T, hs)[rows])
+    q, do, k, v = pick("q", q_heads), pick("do", q_heads), pick("k", kv_heads), pick("v", kv_heads)
+    sub_cu = np.concatenate([[0], np.cumsum(sub_lens)]).astype(np.int32)
+    t0 = time.perf_counter()
+    oracle.attn_fwd(q, k, v, sub_cu)
+    oracle.attn_bwd_dq(q, k, v, do, sub_cu)
+    oracle.attn_bwd_dkdv(q, k, v, do, sub_cu)
+    dt = time.perf_counter() - t0
+    flops = len(q_heads) * pairs * (2 * (w.d_qk + w.d_v) + 2 * (3 * w.d_qk + 2 * w.d_v))
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.oracle_threads(),
+            "kind": "oracle", "seconds": dt,
+            "sample": "%s (%d tokens, %d causal pairs), %d query heads / %d kv heads, fwd+bwd in fp64"
+                      % (what, int(sum(sub_lens)), pairs, len(q_heads), len(kv_heads))}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=3, help="workload 1..5 (default 3: the mixed 32K pack)")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); --gpus %d is not "
+              "supported. Use --gpus 1." % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import hbp_workloads as wl
+    import paper_2503_07680_amd as H
+    from paper_2503_07680_amd.runner import PackedAttention
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(1)
+    H.load_library()
+    w = wl.workload(args.config, args.seed)
+    pa = PackedAttention(w.lengths, w.pack_len, w.n_q_heads, w.n_kv_heads, w.d_qk, w.d_v, with_profile=True)
+    T = pa.T
+    dev = {t: pa.to_device_bf16(wl.workload_tensor_bits(w, t, T)) for t in ("q", "k", "v", "do")}
+    lens = np.diff(pa.cu).astype(np.int64)
+    pairs = int((lens * (lens + 1) // 2).sum())
+    fwd_flops = w.n_q_heads * pairs * 2 * (w.d_qk + w.d_v)
+    bwd_flops = w.n_q_heads * pairs * 2 * (3 * w.d_qk + 2 * w.d_v)
+
+    ev = HipEvents()
+    stream = int(torch.cuda.current_stream().cuda_stream)
+    K = args.steps
+    f_ev = [(ev.create(), ev.create()) for _ in range(K)]
+    b_ev = [(ev.create(), ev.create()) for _ in range(K)]
+    e0, e1 = ev.create(), ev.create()
+
+    def step(i=None):
+        if i is not None:
+            H.hbp_set_kernel_events(H.HBP_FWD, *f_ev[i])
+            H.hbp_set_kernel_events(H.HBP_BWD, *b_ev[i])
+        pa.forward(dev["q"], dev["k"], dev["v"])
+        pa.backward(dev["q"], dev["k"], dev["v"], dev["do"])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev.record(e0, stream)
+    t_host = time.perf_counter()
+    for i in range(K):
+        step(i)
+    ev.record(e1, stream)
+    torch.cuda.synchronize()
+    host_ms = (time.perf_counter() - t_host) * 1e3
+    H.hbp_set_kernel_events(H.HBP_FWD, None, None)
+    H.hbp_set_kernel_events(H.HBP_BWD, None, None)
+    total_ms = ev.elapsed_ms(e0, e1)
+    ms_per_step = total_ms / K
+    fwd_k = np.array([ev.elapsed_ms(a, b) for a, b in f_ev])
+    bwd_k = np.array([ev.elapsed_ms(a, b) for a, b in b_ev])
+
+    # one extra, untimed, profiled step: per-CU busy time
+    pa.forward(dev["q"], dev["k"], dev["v"], profile=True)
+    pa.backward(dev["q"], dev["k"], dev["v"], dev["do"], profile=True)
+    torch.cuda.synchronize()
+    spread_f = busy_spread(pa.profile_records(H.HBP_FWD))
+    spread_b = busy_spread(pa.profile_records(H.HBP_BWD))
+
+    value = (fwd_flops + bwd_flops) / (ms_per_step * 1e-3) / 1e12
+    bwd_tf = bwd_flops / (bwd_k.mean() * 1e-3) / 1e12
+    fwd_tf = fwd_flops / (fwd_k.mean() * 1e-3) / 1e12
+    out = {
+        "metric": "useful TFLOP/s fwd+bwd packed varlen attention (1 GPU) + % of bf16 MFMA peak",
+        "value": value, "unit": "TFLOP/s", "pct_of_bf16_mfma_peak": 100.0 * value / PEAK_BF16_TFLOPS,
+        "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "config %d: %s (%s)" % (args.config, w.name, w.note), "seed": args.seed,
+                   "total_tokens": T, "n_samples": pa.n_samples, "n_q_heads": w.n_q_heads,
+                   "n_kv_heads": w.n_kv_heads, "d_qk": w.d_qk, "d_v": w.d_v, "causal_pairs": pairs,
+                   "pack_cost_sum_s2": pa.pack_cost, "useful_tflop_fwd": fwd_flops / 1e12,
+                   "useful_tflop_bwd": bwd_flops / 1e12},
+        "kernels": {"fwd_ms_avg": float(fwd_k.mean()), "fwd_ms_min": float(fwd_k.min()),
+                    "fwd_tflops": fwd_tf, "bwd_main_ms_avg": float(bwd_k.mean()),
+                    "bwd_main_ms_min": float(bwd_k.min()), "bwd_main_tflops": bwd_tf,
+                    "host_ms_per_step": host_ms / K},
+        "roofline": {"kernel": "bwd_kernel (key-tile persistent kernel)", "bound": "mfma",
+                     "achieved": bwd_tf, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": bwd_tf / PEAK_BF16_TFLOPS, "traffic": None},
+        "busy_time_spread": {"fwd": spread_f, "bwd": spread_b},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, pa.cu)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

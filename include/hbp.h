@@ -163,6 +163,17 @@ hbp_status hbp_varlen_attn_bwd(const hbp_attn_desc* desc, const void* q, const v
                                void* workspace, size_t workspace_bytes,
                                hbp_profile_rec* profile_or_null, void* stream);
 
+/*
+ * hbp_set_kernel_events — measurement hook.  When both events are non-NULL, every later call of
+ * the chosen entry point (which = HBP_FWD / HBP_BWD) records `start` on its stream immediately
+ * before, and `stop` immediately after, its persistent main kernel (the forward kernel; the
+ * key-tile kernel of the backward), so a caller can time that one launch with
+ * hipEventElapsedTime.  Events are hipEvent_t passed as void*, owned by the caller; pass NULLs to
+ * switch the hook off.  Process-wide state, not thread safe.  Returns HBP_ERR_INVALID_ARG for a
+ * bad `which` or when exactly one event is NULL.
+ */
+hbp_status hbp_set_kernel_events(int32_t which, void* start_event, void* stop_event);
+
 #ifdef __cplusplus
 }
 #endif

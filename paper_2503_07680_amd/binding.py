@@ -15,7 +15,8 @@ HBP_FWD, HBP_BWD = 0, 1
 HBP_TILES_QUERY, HBP_TILES_KEY = 0, 1
 
 EXPORTED_SYMBOLS = ["hbp_status_string", "hbp_pack_plan", "hbp_tile_rows", "hbp_workspace_bytes",
-                    "hbp_profile_capacity", "hbp_varlen_attn_fwd", "hbp_varlen_attn_bwd"]
+                    "hbp_profile_capacity", "hbp_varlen_attn_fwd", "hbp_varlen_attn_bwd",
+                    "hbp_set_kernel_events"]
 
 # numpy view of hbp_profile_rec
 PROFILE_DTYPE = np.dtype([("hw_id", "<u4"), ("xcc_id", "<u4"), ("n_items", "<u4"), ("reserved", "<u4"),
@@ -74,6 +75,8 @@ def load_library():
     lib.hbp_varlen_attn_bwd.restype = i32
     lib.hbp_varlen_attn_bwd.argtypes = [descp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp,
                                         ctypes.c_size_t, vp, vp]
+    lib.hbp_set_kernel_events.restype = i32
+    lib.hbp_set_kernel_events.argtypes = [i32, vp, vp]
     _lib = lib
     return lib
 
@@ -165,3 +168,10 @@ def hbp_varlen_attn_bwd(desc: AttnDesc, q, k, v, o, lse, d_o, cu_seqlens, kv_til
         0 if workspace is None else _nbytes(workspace), _ptr(profile), stream)
     if st != 0:
         raise HbpError(st, "hbp_varlen_attn_bwd")
+
+
+def hbp_set_kernel_events(which: int, start_event: Optional[int], stop_event: Optional[int]) -> None:
+    """Raw hipEvent_t handles (ints) recorded around the main kernel of later calls; None = off."""
+    st = load_library().hbp_set_kernel_events(int(which), start_event, stop_event)
+    if st != 0:
+        raise HbpError(st, "hbp_set_kernel_events")

@@ -68,6 +68,8 @@ float resolve_scale(const hbp_attn_desc* d) {
   return d->softmax_scale > 0.f ? d->softmax_scale : 1.0f / std::sqrt((float)d->d_qk);
 }
 
+hipEvent_t g_events[2][2] = {{nullptr, nullptr}, {nullptr, nullptr}};
+
 int grid_for(int64_t n_items, int blocks_per_cu) {
   const int64_t cap = (int64_t)kNumCU * blocks_per_cu;
   return (int)(n_items < cap ? n_items : cap);
@@ -86,6 +88,14 @@ extern "C" const char* hbp_status_string(hbp_status s) {
     case HBP_ERR_DEVICE: return "HIP runtime error at launch";
     default: return "unknown status";
   }
+}
+
+extern "C" hbp_status hbp_set_kernel_events(int32_t which, void* start_event, void* stop_event) {
+  if (which != HBP_FWD && which != HBP_BWD) return HBP_ERR_INVALID_ARG;
+  if ((start_event == nullptr) != (stop_event == nullptr)) return HBP_ERR_INVALID_ARG;
+  g_events[which][0] = static_cast<hipEvent_t>(start_event);
+  g_events[which][1] = static_cast<hipEvent_t>(stop_event);
+  return HBP_OK;
 }
 
 extern "C" hbp_status hbp_tile_rows(int32_t d_qk, int32_t d_v, int32_t which, int32_t* rows_out) {
@@ -155,7 +165,7 @@ extern "C" hbp_status hbp_varlen_attn_fwd(const hbp_attn_desc* desc, const void*
   hipStream_t hs = static_cast<hipStream_t>(stream);
   if (hbp::launch_zero_counter(p.counter, hs) != 0) return HBP_ERR_DEVICE;
   const int grid = grid_for((int64_t)n_q_tiles * p.Hq, fwd_blocks_per_cu(desc->d_qk));
-  if (hbp::launch_fwd(desc->d_qk, desc->d_v, p, grid, hs) != 0) return HBP_ERR_DEVICE;
+  if (hbp::launch_fwd(desc->d_qk, desc->d_v, p, grid, hs, g_events[HBP_FWD][0], g_events[HBP_FWD][1]) != 0) return HBP_ERR_DEVICE;
   return HBP_OK;
 }
 
@@ -210,7 +220,8 @@ extern "C" hbp_status hbp_varlen_attn_bwd(const hbp_attn_desc* desc, const void*
   p.prof = profile;
 
   const int grid = grid_for((int64_t)n_kv_tiles * p.Hkv, 1);
-  if (hbp::launch_bwd(desc->d_qk, desc->d_v, p, grid, static_cast<hipStream_t>(stream)) != 0)
+  if (hbp::launch_bwd(desc->d_qk, desc->d_v, p, grid, static_cast<hipStream_t>(stream), g_events[HBP_BWD][0],
+                      g_events[HBP_BWD][1]) != 0)
     return HBP_ERR_DEVICE;
   return HBP_OK;
 }

@@ -374,7 +374,7 @@ __global__ __launch_bounds__(kThreads) void bwd_convert_kernel(const BwdParams p
 }
 
 template <int DQK, int DV>
-static int launch_bwd_t(const BwdParams& p, int grid, hipStream_t s) {
+static int launch_bwd_t(const BwdParams& p, int grid, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
   const int64_t rh = (int64_t)p.T * p.Hq;
   const int64_t pre_threads = rh * (DV / 8);
   const int64_t cvt_threads = rh * (DQK / 8);
@@ -384,9 +384,11 @@ static int launch_bwd_t(const BwdParams& p, int grid, hipStream_t s) {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return (int)e;
   if (grid > 0) {
+    if (ev0 && hipEventRecord(ev0, s) != hipSuccess) return (int)hipErrorInvalidValue;
     hipLaunchKernelGGL((bwd_kernel<DQK, DV>), dim3(grid), dim3(kThreads), 0, s, p);
     e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
+    if (ev1 && hipEventRecord(ev1, s) != hipSuccess) return (int)hipErrorInvalidValue;
   }
   if (cvt_grid > 0) {
     hipLaunchKernelGGL((bwd_convert_kernel<DQK>), dim3(cvt_grid), dim3(kThreads), 0, s, p);
@@ -395,10 +397,11 @@ static int launch_bwd_t(const BwdParams& p, int grid, hipStream_t s) {
   return (int)e;
 }
 
-int launch_bwd(int d_qk, int d_v, const BwdParams& p, int grid, hipStream_t s) {
-  if (d_qk == 64 && d_v == 64) return launch_bwd_t<64, 64>(p, grid, s);
-  if (d_qk == 128 && d_v == 128) return launch_bwd_t<128, 128>(p, grid, s);
-  if (d_qk == 192 && d_v == 128) return launch_bwd_t<192, 128>(p, grid, s);
+int launch_bwd(int d_qk, int d_v, const BwdParams& p, int grid, hipStream_t s, hipEvent_t ev0,
+               hipEvent_t ev1) {
+  if (d_qk == 64 && d_v == 64) return launch_bwd_t<64, 64>(p, grid, s, ev0, ev1);
+  if (d_qk == 128 && d_v == 128) return launch_bwd_t<128, 128>(p, grid, s, ev0, ev1);
+  if (d_qk == 192 && d_v == 128) return launch_bwd_t<192, 128>(p, grid, s, ev0, ev1);
   return (int)hipErrorInvalidValue;
 }
 

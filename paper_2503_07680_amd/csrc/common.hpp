@@ -87,8 +87,9 @@ struct BwdParams {
 };
 
 // launchers implemented in the .hip files; return hipError_t as int
-int launch_fwd(int d_qk, int d_v, const FwdParams& p, int grid, hipStream_t s);
-int launch_bwd(int d_qk, int d_v, const BwdParams& p, int grid, hipStream_t s);
+// ev0/ev1: optional events recorded around the persistent main kernel
+int launch_fwd(int d_qk, int d_v, const FwdParams& p, int grid, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
+int launch_bwd(int d_qk, int d_v, const BwdParams& p, int grid, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
 int launch_zero_counter(int32_t* counter, hipStream_t s);
 
 }  // namespace hbp

@@ -251,7 +251,9 @@ int launch_zero_counter(int32_t* counter, hipStream_t s) {
   return (int)hipGetLastError();
 }
 
-int launch_fwd(int d_qk, int d_v, const FwdParams& p, int grid, hipStream_t s) {
+int launch_fwd(int d_qk, int d_v, const FwdParams& p, int grid, hipStream_t s, hipEvent_t ev0,
+               hipEvent_t ev1) {
+  if (ev0 && hipEventRecord(ev0, s) != hipSuccess) return (int)hipErrorInvalidValue;
   if (d_qk == 64 && d_v == 64)
     hipLaunchKernelGGL((fwd_kernel<64, 64>), dim3(grid), dim3(kThreads), 0, s, p);
   else if (d_qk == 128 && d_v == 128)
@@ -260,7 +262,9 @@ int launch_fwd(int d_qk, int d_v, const FwdParams& p, int grid, hipStream_t s) {
     hipLaunchKernelGGL((fwd_kernel<192, 128>), dim3(grid), dim3(kThreads), 0, s, p);
   else
     return (int)hipErrorInvalidValue;
-  return (int)hipGetLastError();
+  const hipError_t e = hipGetLastError();
+  if (e == hipSuccess && ev1 && hipEventRecord(ev1, s) != hipSuccess) return (int)hipErrorInvalidValue;
+  return (int)e;
 }
 
 }  // namespace hbp

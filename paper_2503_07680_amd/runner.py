@@ -63,9 +63,10 @@ class PackedAttention:
     def _stream(self) -> int:
         return int(torch.cuda.current_stream(self.device).cuda_stream)
 
-    def forward(self, q, k, v):
+    def forward(self, q, k, v, profile: bool = False):
         B.hbp_varlen_attn_fwd(self.desc, q, k, v, self.cu_dev, self.q_tiles_dev, len(self.q_tiles),
-                              self.o, self.lse, self.ws_fwd, self.prof_fwd, self._stream())
+                              self.o, self.lse, self.ws_fwd, self.prof_fwd if profile else None,
+                              self._stream())
         return self.o, self.lse
 
     def alloc_backward(self):
@@ -76,11 +77,11 @@ class PackedAttention:
             self.dk = torch.zeros((T, self.Hkv, self.d_qk), dtype=bf, device=dev)
             self.dv = torch.zeros((T, self.Hkv, self.d_v), dtype=bf, device=dev)
 
-    def backward(self, q, k, v, d_o):
+    def backward(self, q, k, v, d_o, profile: bool = False):
         self.alloc_backward()
         B.hbp_varlen_attn_bwd(self.desc, q, k, v, self.o, self.lse, d_o, self.cu_dev, self.kv_tiles_dev,
-                              len(self.kv_tiles), self.dq, self.dk, self.dv, self.ws_bwd, self.prof_bwd,
-                              self._stream())
+                              len(self.kv_tiles), self.dq, self.dk, self.dv, self.ws_bwd,
+                              self.prof_bwd if profile else None, self._stream())
         return self.dq, self.dk, self.dv
 
     def profile_records(self, which: int) -> np.ndarray:
