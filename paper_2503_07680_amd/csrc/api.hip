@@ -13,7 +13,7 @@ bool dims_supported(int d_qk, int d_v) {
   return (d_qk == 64 && d_v == 64) || (d_qk == 128 && d_v == 128) || (d_qk == 192 && d_v == 128);
 }
 
-int fwd_blocks_per_cu(int d_qk) { return d_qk <= 64 ? 2 : 1; }
+int fwd_blocks_per_cu(int) { return 2; }
 
 struct Strides {
   int64_t q_st, q_sh, k_st, k_sh, v_st, v_sh, o_st, o_sh;

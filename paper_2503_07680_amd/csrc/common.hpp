@@ -23,10 +23,13 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
 union Frag {
   bf16x8 v;
   u32x4 u;
   uint32_t w[4];
+  s16x4 h[2];
 };
 
 // two fp32 -> packed bf16 pair (round to nearest even), low half = a
@@ -42,6 +45,63 @@ __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w 
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
 __device__ __forceinline__ float xor32(float x) { return __shfl_xor(x, 32, 64); }
+
+// max over a lane and its partner lane^32 (one v_permlane32_swap: r[0] = {lo half of x, lo half of
+// x}, r[1] = {hi half of x, hi half of x} when both inputs are x)
+__device__ __forceinline__ float max_with_other_half(float x) {
+  const uint32_t u = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+// ---- LDS tiles in their natural [row][dim] layout, 16-byte chunks XOR-swizzled -----------------
+// Chunk c of row r sits at chunk position c ^ (g(r) & MASK), g(r) = ((r&3)<<2) | ((r>>2)&3).
+// With 256-byte rows this serves both access patterns without bank conflicts: 16 consecutive
+// rows read at one chunk index (row-major MFMA operand, 16-byte reads) hit 16 distinct chunk
+// positions, and the 8 rows x 4 consecutive chunks of one transposing read spread over all four
+// 64-byte quarters of the bank line twice.
+__device__ __forceinline__ int swz_g(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
+template <int D>
+__device__ __forceinline__ int swz(int chunk, int row) {
+  constexpr int MASK = (D / 8 == 16) ? 15 : 7;
+  return chunk ^ (swz_g(row) & MASK);
+}
+
+// Asynchronous global -> LDS copy of a [ROWS][D] bf16 tile (row stride `stride` elements), with
+// the swizzle applied on the global side: each wave instruction fills 1 KiB of contiguous LDS
+// (lane i -> bytes 16i..16i+15).  Rows >= rows_valid re-read the last valid row (never out of
+// bounds; their products are masked by the caller).  lds_tile must be 1 KiB aligned.
+template <int D, int ROWS>
+__device__ __forceinline__ void async_tile_load(const uint16_t* g, int64_t stride, int rows_valid,
+                                                char* lds_tile, int wave, int lane) {
+  constexpr int RB = D * 2;
+  constexpr int N_INSTR = ROWS * RB / 1024;
+  const int last = rows_valid - 1;
+#pragma unroll
+  for (int ii = 0; ii < (N_INSTR + 3) / 4; ++ii) {
+    const int inst = wave + 4 * ii;
+    if (N_INSTR % 4 != 0 && inst >= N_INSTR) break;
+    const int pos = inst * 1024 + lane * 16;
+    const int row = pos / RB, cpos = (pos % RB) / 16;
+    const int c = swz<D>(cpos, row);
+    const int grow = row < last ? row : last;
+    const uint16_t* src = g + (int64_t)grow * stride + 8 * c;
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                     (__attribute__((address_space(3))) void*)(lds_tile + inst * 1024),
+                                     16, 0, 0);
+  }
+}
+
+// all of this wave's outstanding global loads (including global -> LDS copies) have completed
+__device__ __forceinline__ void wait_async_loads() {
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0), expcnt and lgkmcnt left at their maxima
+}
+
+// ds_read_b64_tr_b16: within each group of 16 lanes, lane i receives element i%4 of the 8-byte
+// words addressed by lanes i/4, i/4+4, i/4+8, i/4+12 of the group.
+__device__ __forceinline__ s16x4 lds_read_tr16(const char* addr) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)addr);
+}
 
 // Position of contraction index w (0..15) inside a 16-element chunk of a transposed LDS tile.
 // An MFMA whose B operand is taken straight from an accumulator sees, in lane half hh, the

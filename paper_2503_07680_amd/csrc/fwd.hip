@@ -8,37 +8,56 @@
 //                    the accumulator then has one query per lane column, its keys in-lane, so
 //                    the row max/sum needs a single exchange with lane^32.
 //   P^T -> bf16      used directly as the B operand of the next product (no shuffle);
-//   O^T += V^T P^T   V tile stored transposed in LDS with the contraction index permuted to
-//                    match the accumulator's row order.
-// exp is taken in base 2 with scale*log2(e) folded into one multiplier.
+//   O^T += V^T P^T   V tile kept in its natural [key][dim] layout in LDS and read with the
+//                    transposing LDS load, in the key order the accumulator rows have.
+// K and V tiles go global -> LDS directly (no staging registers), double buffered, with an XOR
+// swizzle of the 16-byte chunks applied on the global side.  exp is taken in base 2 with
+// scale*log2(e) folded into one multiplier.
 #include "common.hpp"
 
 namespace hbp {
 
 template <int DQK, int DV>
-__global__ __launch_bounds__(kThreads, (DQK <= 64 ? 2 : 1)) void fwd_kernel(const FwdParams p) {
+__global__ __launch_bounds__(kThreads, 2) void fwd_kernel(const FwdParams p) {
   constexpr int BM = 128, BN = 64;
-  constexpr int KP = DQK + 8;                        // LDS pitch of a K row (elements)
-  constexpr int VP = BN + 8;                         // LDS pitch of a V^T row
-  constexpr int NC = DQK / 16;                       // contraction chunks of QK^T
-  constexpr int NEB = DV / 32;                       // 32-wide blocks of the head dim of V
-  constexpr int K_PIECES = BN * (DQK / 8) / kThreads;  // 16-byte pieces per thread
-  constexpr int V_UNITS = (BN / 4) * (DV / 2) / kThreads;  // (4 keys x 2 cols) units per thread
+  constexpr int KRB = DQK * 2, VRB = DV * 2;  // bytes per LDS row
+  constexpr int K_TILE = BN * KRB, V_TILE = BN * VRB;
+  constexpr int NC = DQK / 16;   // contraction chunks of QK^T
+  constexpr int NEB = DV / 32;   // 32-wide blocks of the head dim of V
 
-  __shared__ __attribute__((aligned(16))) uint16_t Ks[BN * KP];
-  __shared__ __attribute__((aligned(16))) uint16_t Vt[DV * VP];
-  __shared__ int s_item;
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  // [K buf0][K buf1][V buf0][V buf1]
+  char* const k_lds = smem;
+  char* const v_lds = smem + 2 * K_TILE;
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
+
+  // per-lane LDS byte offsets of the A operands (row part that does not depend on the 32-key block)
+  int koff[NC];
+#pragma unroll
+  for (int c = 0; c < NC; ++c) koff[c] = l32 * KRB + swz<DQK>(2 * c + hh, l32) * 16;
+  int voff[2][NEB];
+  {
+    const int G = lane >> 4, s = lane & 15;
+    const int k8 = 4 * hh + (s >> 2);
+#pragma unroll
+    for (int r = 0; r < 2; ++r)
+#pragma unroll
+      for (int eb = 0; eb < NEB; ++eb) {
+        const int c = 4 * eb + 2 * (G & 1) + ((s & 3) >> 1);
+        voff[r][eb] = (8 * r + k8) * VRB + swz<DV>(c, 8 * r + k8) * 16 + (s & 1) * 8;
+      }
+  }
 
   uint32_t n_done = 0;
   uint64_t t_first = 0, t_last = 0, t_busy = 0;
 
   for (;;) {
-    if (tid == 0) s_item = atomicAdd(p.counter, 1);
+    __syncthreads();  // all LDS reads of the previous item are finished
+    if (tid == 0) *(volatile int*)smem = atomicAdd(p.counter, 1);
     __syncthreads();
-    const int item = s_item;
+    const int item = *(volatile int*)smem;
     __syncthreads();
     if (item >= p.n_tiles * p.Hq) break;
     uint64_t t0 = 0;
@@ -65,6 +84,21 @@ __global__ __launch_bounds__(kThreads, (DQK <= 64 ? 2 : 1)) void fwd_kernel(cons
       const bool row_valid = my_row < r1;
       const bool wave_active = r0 + 32 * wave < r1;
 
+      const int n_keys = r1 - s0;  // keys 0..n_keys-1 (in-sample) are needed by this tile
+      const int nkt = (n_keys + BN - 1) / BN;
+      const uint16_t* kbase = p.k + (int64_t)s0 * p.k_st + (int64_t)kh * p.k_sh;
+      const uint16_t* vbase = p.v + (int64_t)s0 * p.v_st + (int64_t)kh * p.v_sh;
+
+      auto issue = [&](int kt) {
+        const int k_off = kt * BN;
+        const int valid = n_keys - k_off;  // >= 1
+        async_tile_load<DQK, BN>(kbase + (int64_t)k_off * p.k_st, p.k_st, valid,
+                                 k_lds + (kt & 1) * K_TILE, wave, lane);
+        async_tile_load<DV, BN>(vbase + (int64_t)k_off * p.v_st, p.v_st, valid,
+                                v_lds + (kt & 1) * V_TILE, wave, lane);
+      };
+      issue(0);
+
       // Q fragments (B operand of S^T = K Q^T): lane holds query l32, dims 16c+8hh..+7
       Frag qf[NC];
       {
@@ -83,65 +117,15 @@ __global__ __launch_bounds__(kThreads, (DQK <= 64 ? 2 : 1)) void fwd_kernel(cons
         for (int i = 0; i < 16; ++i) oacc[eb][i] = 0.f;
       float m_run = -INFINITY, l_run = 0.f;
 
-      const int n_keys = r1 - s0;  // keys 0..n_keys-1 (in-sample) are needed by this tile
-      const int nkt = (n_keys + BN - 1) / BN;
-      const uint16_t* kbase = p.k + (int64_t)s0 * p.k_st + (int64_t)kh * p.k_sh;
-      const uint16_t* vbase = p.v + (int64_t)s0 * p.v_st + (int64_t)kh * p.v_sh;
-
-      u32x4 kreg[K_PIECES];
-      uint32_t vreg[V_UNITS][4];
-
-      auto load_tile = [&](int kt) {
-        const int k_off = kt * BN;
-#pragma unroll
-        for (int i = 0; i < K_PIECES; ++i) {
-          const int pi = tid + kThreads * i;
-          const int row = pi / (DQK / 8), c8 = pi % (DQK / 8);
-          if (k_off + row < n_keys)
-            kreg[i] = *(const u32x4*)(kbase + (int64_t)(k_off + row) * p.k_st + 8 * c8);
-          else
-            kreg[i] = u32x4{0, 0, 0, 0};
-        }
-#pragma unroll
-        for (int i = 0; i < V_UNITS; ++i) {
-          const int u = tid + kThreads * i;
-          const int cp = u % (DV / 2), rg = u / (DV / 2);
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const int row = k_off + 4 * rg + j;
-            vreg[i][j] = row < n_keys ? *(const uint32_t*)(vbase + (int64_t)row * p.v_st + 2 * cp) : 0u;
-          }
-        }
-      };
-      auto store_tile = [&]() {
-#pragma unroll
-        for (int i = 0; i < K_PIECES; ++i) {
-          const int pi = tid + kThreads * i;
-          const int row = pi / (DQK / 8), c8 = pi % (DQK / 8);
-          *(u32x4*)&Ks[row * KP + 8 * c8] = kreg[i];
-        }
-#pragma unroll
-        for (int i = 0; i < V_UNITS; ++i) {
-          const int u = tid + kThreads * i;
-          const int cp = u % (DV / 2), rg = u / (DV / 2);
-          const int pos = 16 * (rg >> 2) + tslot(4 * (rg & 3));
-          const uint32_t a0 = vreg[i][0], a1 = vreg[i][1], a2 = vreg[i][2], a3 = vreg[i][3];
-          u32x2 lo = {(a0 & 0xffffu) | (a1 << 16), (a2 & 0xffffu) | (a3 << 16)};
-          u32x2 hi = {(a0 >> 16) | (a1 & 0xffff0000u), (a2 >> 16) | (a3 & 0xffff0000u)};
-          *(u32x2*)&Vt[(2 * cp) * VP + pos] = lo;
-          *(u32x2*)&Vt[(2 * cp + 1) * VP + pos] = hi;
-        }
-      };
-
-      load_tile(0);
       for (int kt = 0; kt < nkt; ++kt) {
-        __syncthreads();  // every wave is done reading the previous tile
-        store_tile();
-        __syncthreads();
-        if (kt + 1 < nkt) load_tile(kt + 1);  // in flight while this tile is computed
+        wait_async_loads();
+        __syncthreads();  // tile kt has landed for every wave; tile kt-1 is no longer read
+        if (kt + 1 < nkt) issue(kt + 1);
 
         const int k_off = kt * BN;
         if (!wave_active || k_off > qw0 + 31) continue;  // nothing at or below the diagonal
+        const char* kt_lds = k_lds + (kt & 1) * K_TILE;
+        const char* vt_lds = v_lds + (kt & 1) * V_TILE;
 
         f32x16 sacc[2];
 #pragma unroll
@@ -151,7 +135,7 @@ __global__ __launch_bounds__(kThreads, (DQK <= 64 ? 2 : 1)) void fwd_kernel(cons
 #pragma unroll
           for (int c = 0; c < NC; ++c) {
             Frag kf;
-            kf.u = *(const u32x4*)&Ks[(32 * blk + l32) * KP + 16 * c + 8 * hh];
+            kf.u = *(const u32x4*)(kt_lds + 32 * blk * KRB + koff[c]);
             sacc[blk] = mfma32(kf.v, qf[c].v, sacc[blk]);
           }
         }
@@ -171,7 +155,7 @@ __global__ __launch_bounds__(kThreads, (DQK <= 64 ? 2 : 1)) void fwd_kernel(cons
             sacc[blk][i] = x;
             mx = fmaxf(mx, x);
           }
-        mx = fmaxf(mx, xor32(mx));
+        mx = max_with_other_half(mx);
         const float m_new = fmaxf(m_run, mx);  // finite: key 0 of the sample is visible to every row
         const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
         m_run = m_new;
@@ -200,7 +184,9 @@ __global__ __launch_bounds__(kThreads, (DQK <= 64 ? 2 : 1)) void fwd_kernel(cons
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
               Frag vf;
-              vf.u = *(const u32x4*)&Vt[(32 * eb + l32) * VP + 32 * blk + 16 * j + 8 * hh];
+              const char* base = vt_lds + (32 * blk + 16 * j) * VRB;
+              vf.h[0] = lds_read_tr16(base + voff[0][eb]);
+              vf.h[1] = lds_read_tr16(base + voff[1][eb]);
               oacc[eb] = mfma32(vf.v, pf[blk][j].v, oacc[eb]);
             }
       }
@@ -251,20 +237,30 @@ int launch_zero_counter(int32_t* counter, hipStream_t s) {
   return (int)hipGetLastError();
 }
 
+template <int DQK, int DV>
+static int launch_fwd_t(const FwdParams& p, int grid, hipStream_t s) {
+  constexpr int lds_bytes = 2 * 64 * (DQK * 2 + DV * 2);
+  static bool attr_set = false;
+  if (!attr_set) {
+    const hipError_t e = hipFuncSetAttribute((const void*)fwd_kernel<DQK, DV>,
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    if (e != hipSuccess) return (int)e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((fwd_kernel<DQK, DV>), dim3(grid), dim3(kThreads), lds_bytes, s, p);
+  return (int)hipGetLastError();
+}
+
 int launch_fwd(int d_qk, int d_v, const FwdParams& p, int grid, hipStream_t s, hipEvent_t ev0,
                hipEvent_t ev1) {
   if (ev0 && hipEventRecord(ev0, s) != hipSuccess) return (int)hipErrorInvalidValue;
-  if (d_qk == 64 && d_v == 64)
-    hipLaunchKernelGGL((fwd_kernel<64, 64>), dim3(grid), dim3(kThreads), 0, s, p);
-  else if (d_qk == 128 && d_v == 128)
-    hipLaunchKernelGGL((fwd_kernel<128, 128>), dim3(grid), dim3(kThreads), 0, s, p);
-  else if (d_qk == 192 && d_v == 128)
-    hipLaunchKernelGGL((fwd_kernel<192, 128>), dim3(grid), dim3(kThreads), 0, s, p);
-  else
-    return (int)hipErrorInvalidValue;
-  const hipError_t e = hipGetLastError();
-  if (e == hipSuccess && ev1 && hipEventRecord(ev1, s) != hipSuccess) return (int)hipErrorInvalidValue;
-  return (int)e;
+  int e;
+  if (d_qk == 64 && d_v == 64) e = launch_fwd_t<64, 64>(p, grid, s);
+  else if (d_qk == 128 && d_v == 128) e = launch_fwd_t<128, 128>(p, grid, s);
+  else if (d_qk == 192 && d_v == 128) e = launch_fwd_t<192, 128>(p, grid, s);
+  else return (int)hipErrorInvalidValue;
+  if (e == 0 && ev1 && hipEventRecord(ev1, s) != hipSuccess) return (int)hipErrorInvalidValue;
+  return e;
 }
 
 }  // namespace hbp
