@@ -148,12 +148,14 @@ def main():
     K = args.steps
     f_ev = [(ev.create(), ev.create()) for _ in range(K)]
     b_ev = [(ev.create(), ev.create()) for _ in range(K)]
+    q_ev = [(ev.create(), ev.create()) for _ in range(K)]
     e0, e1 = ev.create(), ev.create()
 
     def step(i=None):
         if i is not None:
             H.hbp_set_kernel_events(H.HBP_FWD, *f_ev[i])
             H.hbp_set_kernel_events(H.HBP_BWD, *b_ev[i])
+            H.hbp_set_kernel_events(H.HBP_BWD_DQ, *q_ev[i])
         pa.forward(dev["q"], dev["k"], dev["v"])
         pa.backward(dev["q"], dev["k"], dev["v"], dev["do"])
 
@@ -169,10 +171,12 @@ def main():
     host_ms = (time.perf_counter() - t_host) * 1e3
     H.hbp_set_kernel_events(H.HBP_FWD, None, None)
     H.hbp_set_kernel_events(H.HBP_BWD, None, None)
+    H.hbp_set_kernel_events(H.HBP_BWD_DQ, None, None)
     total_ms = ev.elapsed_ms(e0, e1)
     ms_per_step = total_ms / K
     fwd_k = np.array([ev.elapsed_ms(a, b) for a, b in f_ev])
     bwd_k = np.array([ev.elapsed_ms(a, b) for a, b in b_ev])
+    dq_k = np.array([ev.elapsed_ms(a, b) for a, b in q_ev])
 
     # one extra, untimed, profiled step: per-CU busy time
     pa.forward(dev["q"], dev["k"], dev["v"], profile=True)
@@ -180,9 +184,15 @@ def main():
     torch.cuda.synchronize()
     spread_f = busy_spread(pa.profile_records(H.HBP_FWD))
     spread_b = busy_spread(pa.profile_records(H.HBP_BWD))
+    spread_q = busy_spread(pa.profile_records(H.HBP_BWD_DQ))
 
     value = (fwd_flops + bwd_flops) / (ms_per_step * 1e-3) / 1e12
-    bwd_tf = bwd_flops / (bwd_k.mean() * 1e-3) / 1e12
+    # flops of the launches themselves: the dK/dV kernel does 4 of the backward's products
+    # (S, dP, dV, dK), the dQ kernel 3 (S and dP again, dQ); only 5 of those 7 count as useful
+    per_pair = lambda n_qk, n_v: w.n_q_heads * pairs * 2 * (n_qk * w.d_qk + n_v * w.d_v)
+    dkdv_flops, dq_flops = per_pair(2, 2), per_pair(2, 1)
+    bwd_tf = dkdv_flops / (bwd_k.mean() * 1e-3) / 1e12
+    dq_tf = dq_flops / (dq_k.mean() * 1e-3) / 1e12
     fwd_tf = fwd_flops / (fwd_k.mean() * 1e-3) / 1e12
     out = {
         "metric": "useful TFLOP/s fwd+bwd packed varlen attention (1 GPU) + % of bf16 MFMA peak",
@@ -196,13 +206,16 @@ def main():
                    "pack_cost_sum_s2": pa.pack_cost, "useful_tflop_fwd": fwd_flops / 1e12,
                    "useful_tflop_bwd": bwd_flops / 1e12},
         "kernels": {"fwd_ms_avg": float(fwd_k.mean()), "fwd_ms_min": float(fwd_k.min()),
-                    "fwd_tflops": fwd_tf, "bwd_main_ms_avg": float(bwd_k.mean()),
-                    "bwd_main_ms_min": float(bwd_k.min()), "bwd_main_tflops": bwd_tf,
+                    "fwd_tflops": fwd_tf, "bwd_dkdv_ms_avg": float(bwd_k.mean()),
+                    "bwd_dkdv_ms_min": float(bwd_k.min()), "bwd_dkdv_tflops": bwd_tf,
+                    "bwd_dq_ms_avg": float(dq_k.mean()), "bwd_dq_ms_min": float(dq_k.min()),
+                    "bwd_dq_tflops": dq_tf,
                     "host_ms_per_step": host_ms / K},
-        "roofline": {"kernel": "bwd_kernel (key-tile persistent kernel)", "bound": "mfma",
+        "roofline": {"kernel": "bwd_dkdv_kernel (key-tile persistent kernel; S, dP, dV, dK products)",
+                     "bound": "mfma", "flop_per_launch": dkdv_flops,
                      "achieved": bwd_tf, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": bwd_tf / PEAK_BF16_TFLOPS, "traffic": None},
-        "busy_time_spread": {"fwd": spread_f, "bwd": spread_b},
+        "busy_time_spread": {"fwd": spread_f, "bwd_dkdv": spread_b, "bwd_dq": spread_q},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, pa.cu)

@@ -50,7 +50,7 @@ typedef struct {
 } hbp_tile;
 
 enum { HBP_TILES_QUERY = 0, HBP_TILES_KEY = 1 };
-enum { HBP_FWD = 0, HBP_BWD = 1 };
+enum { HBP_FWD = 0, HBP_BWD = 1, HBP_BWD_DQ = 2 }; /* forward; backward (its dK/dV kernel); backward's dQ kernel */
 
 /*
  * hbp_pack_plan — host only, integer only, deterministic.
@@ -97,8 +97,8 @@ typedef struct {
 hbp_status hbp_tile_rows(int32_t d_qk, int32_t d_v, int32_t which, int32_t* rows_out);
 
 /* Bytes of device workspace a call needs (256-byte aligned base required).
- * which = HBP_FWD or HBP_BWD.  Forward: a scheduler counter.  Backward: the counter, the
- * per-row D = rowsum(dO*O) [Hq,T] fp32 and an fp32 dQ accumulator [T,Hq,d_qk]. */
+ * which = HBP_FWD or HBP_BWD.  Forward: a scheduler counter.  Backward: two counters and the
+ * per-row D = rowsum(dO*O) [Hq,T] fp32. */
 hbp_status hbp_workspace_bytes(const hbp_attn_desc* desc, int32_t which, size_t* bytes_out);
 
 /* Optional per-workgroup record written by the persistent kernels when `profile` != NULL
@@ -113,7 +113,8 @@ typedef struct {
   uint64_t busy_ticks; /* sum over items of (end - start)                                 */
 } hbp_profile_rec;
 
-/* Number of hbp_profile_rec the caller must provide = workgroups launched by fwd / bwd-main. */
+/* Number of hbp_profile_rec the caller must provide = workgroups launched by the kernel named by
+ * which (HBP_FWD, HBP_BWD = the dK/dV kernel, HBP_BWD_DQ = the dQ kernel). */
 hbp_status hbp_profile_capacity(const hbp_attn_desc* desc, int32_t which, int32_t* n_records_out);
 
 /*
@@ -148,26 +149,31 @@ hbp_status hbp_varlen_attn_fwd(const hbp_attn_desc* desc, const void* q, const v
  *   dS = P * (dP - D[r]);  dQ = scale * dS K;  dK = scale * sum_{h in group} dS^T Q;
  *   dV = sum_{h in group} P^T dO
  *
- * Three launches on `stream`: a pre-pass (D, and zeroing of the fp32 dQ accumulator), the
- * persistent key-tile kernel (dK/dV in registers, dQ by fp32 atomics into the workspace, so
- * dQ's summation order is not fixed), and a convert pass (dQ accumulator -> bf16).
+ * Three launches on `stream`: a pre-pass (D), the persistent key-tile kernel (dK/dV accumulated in
+ * registers over the query blocks and over the query heads of each kv head) and the persistent
+ * query-tile kernel (dQ; it recomputes S and dP).  No atomics: every output element is written
+ * once, results are bit-stable.
+ * q_tiles: the HBP_TILES_QUERY list made with hbp_tile_rows(..., HBP_FWD) (the forward's list);
  * kv_tiles: the HBP_TILES_KEY list made with hbp_tile_rows(..., HBP_BWD).
- * o and lse are the forward's outputs.  Every dK/dV row covered by a tile is written; dQ is
- * written for all T rows.  Same memory placement and error rules as the forward.
+ * o and lse are the forward's outputs.  dK/dV rows covered by a key tile and dQ rows covered by a
+ * query tile are written; others are left untouched.  profile / profile_dq: optional records of
+ * the dK/dV and the dQ kernel.  Same memory placement and error rules as the forward.
  */
 hbp_status hbp_varlen_attn_bwd(const hbp_attn_desc* desc, const void* q, const void* k,
                                const void* v, const void* o, const float* lse, const void* d_o,
                                const int32_t* cu_seqlens,
+                               const hbp_tile* q_tiles, int32_t n_q_tiles,
                                const hbp_tile* kv_tiles, int32_t n_kv_tiles,
                                void* dq, void* dk, void* dv,
                                void* workspace, size_t workspace_bytes,
-                               hbp_profile_rec* profile_or_null, void* stream);
+                               hbp_profile_rec* profile_or_null, hbp_profile_rec* profile_dq_or_null,
+                               void* stream);
 
 /*
  * hbp_set_kernel_events — measurement hook.  When both events are non-NULL, every later call of
- * the chosen entry point (which = HBP_FWD / HBP_BWD) records `start` on its stream immediately
- * before, and `stop` immediately after, its persistent main kernel (the forward kernel; the
- * key-tile kernel of the backward), so a caller can time that one launch with
+ * the entry point that launches the chosen kernel (which = HBP_FWD, HBP_BWD, HBP_BWD_DQ) records
+ * `start` on its stream immediately before, and `stop` immediately after, that persistent kernel
+ * (the forward kernel; the dK/dV kernel; the dQ kernel), so a caller can time that one launch with
  * hipEventElapsedTime.  Events are hipEvent_t passed as void*, owned by the caller; pass NULLs to
  * switch the hook off.  Process-wide state, not thread safe.  Returns HBP_ERR_INVALID_ARG for a
  * bad `which` or when exactly one event is NULL.

@@ -11,7 +11,7 @@ from typing import Optional, Sequence
 
 import numpy as np
 
-HBP_FWD, HBP_BWD = 0, 1
+HBP_FWD, HBP_BWD, HBP_BWD_DQ = 0, 1, 2
 HBP_TILES_QUERY, HBP_TILES_KEY = 0, 1
 
 EXPORTED_SYMBOLS = ["hbp_status_string", "hbp_pack_plan", "hbp_tile_rows", "hbp_workspace_bytes",
@@ -73,8 +73,8 @@ def load_library():
     lib.hbp_varlen_attn_fwd.restype = i32
     lib.hbp_varlen_attn_fwd.argtypes = [descp, vp, vp, vp, vp, vp, i32, vp, vp, vp, ctypes.c_size_t, vp, vp]
     lib.hbp_varlen_attn_bwd.restype = i32
-    lib.hbp_varlen_attn_bwd.argtypes = [descp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp,
-                                        ctypes.c_size_t, vp, vp]
+    lib.hbp_varlen_attn_bwd.argtypes = [descp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, i32, vp, vp, vp, vp,
+                                        ctypes.c_size_t, vp, vp, vp]
     lib.hbp_set_kernel_events.restype = i32
     lib.hbp_set_kernel_events.argtypes = [i32, vp, vp]
     _lib = lib
@@ -159,13 +159,15 @@ def hbp_varlen_attn_fwd(desc: AttnDesc, q, k, v, cu_seqlens, q_tiles, n_q_tiles:
         raise HbpError(st, "hbp_varlen_attn_fwd")
 
 
-def hbp_varlen_attn_bwd(desc: AttnDesc, q, k, v, o, lse, d_o, cu_seqlens, kv_tiles, n_kv_tiles: int,
-                        dq, dk, dv, workspace, profile=None, stream: Optional[int] = None) -> None:
-    """Enqueue the backward (prepass, key-tile kernel, dQ convert) on ``stream``."""
+def hbp_varlen_attn_bwd(desc: AttnDesc, q, k, v, o, lse, d_o, cu_seqlens, q_tiles, n_q_tiles: int,
+                        kv_tiles, n_kv_tiles: int, dq, dk, dv, workspace, profile=None, profile_dq=None,
+                        stream: Optional[int] = None) -> None:
+    """Enqueue the backward (prepass, dK/dV kernel, dQ kernel) on ``stream``."""
     st = load_library().hbp_varlen_attn_bwd(
         ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(d_o), _ptr(cu_seqlens),
-        _ptr(kv_tiles), int(n_kv_tiles), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(workspace),
-        0 if workspace is None else _nbytes(workspace), _ptr(profile), stream)
+        _ptr(q_tiles), int(n_q_tiles), _ptr(kv_tiles), int(n_kv_tiles), _ptr(dq), _ptr(dk), _ptr(dv),
+        _ptr(workspace), 0 if workspace is None else _nbytes(workspace), _ptr(profile), _ptr(profile_dq),
+        stream)
     if st != 0:
         raise HbpError(st, "hbp_varlen_attn_bwd")
 

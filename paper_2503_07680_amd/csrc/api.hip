@@ -13,7 +13,6 @@ bool dims_supported(int d_qk, int d_v) {
   return (d_qk == 64 && d_v == 64) || (d_qk == 128 && d_v == 128) || (d_qk == 192 && d_v == 128);
 }
 
-int fwd_blocks_per_cu(int) { return 2; }
 
 struct Strides {
   int64_t q_st, q_sh, k_st, k_sh, v_st, v_sh, o_st, o_sh;
@@ -53,14 +52,13 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct BwdLayout {
-  size_t d_off, dq_off, total;
+  size_t d_off, total;
 };
 
 BwdLayout bwd_layout(const hbp_attn_desc* d) {
   BwdLayout l;
-  l.d_off = kCounterBytes;
-  l.dq_off = align_up(l.d_off + (size_t)d->n_q_heads * d->total_tokens * sizeof(float), 256);
-  l.total = align_up(l.dq_off + (size_t)d->total_tokens * d->n_q_heads * d->d_qk * sizeof(float), 256);
+  l.d_off = kCounterBytes;  // two counters, 128 bytes apart, in the first 256 bytes
+  l.total = align_up(l.d_off + (size_t)d->n_q_heads * d->total_tokens * sizeof(float), 256);
   return l;
 }
 
@@ -68,7 +66,7 @@ float resolve_scale(const hbp_attn_desc* d) {
   return d->softmax_scale > 0.f ? d->softmax_scale : 1.0f / std::sqrt((float)d->d_qk);
 }
 
-hipEvent_t g_events[2][2] = {{nullptr, nullptr}, {nullptr, nullptr}};
+hipEvent_t g_events[3][2] = {{nullptr, nullptr}, {nullptr, nullptr}, {nullptr, nullptr}};
 
 int grid_for(int64_t n_items, int blocks_per_cu) {
   const int64_t cap = (int64_t)kNumCU * blocks_per_cu;
@@ -91,7 +89,7 @@ extern "C" const char* hbp_status_string(hbp_status s) {
 }
 
 extern "C" hbp_status hbp_set_kernel_events(int32_t which, void* start_event, void* stop_event) {
-  if (which != HBP_FWD && which != HBP_BWD) return HBP_ERR_INVALID_ARG;
+  if (which != HBP_FWD && which != HBP_BWD && which != HBP_BWD_DQ) return HBP_ERR_INVALID_ARG;
   if ((start_event == nullptr) != (stop_event == nullptr)) return HBP_ERR_INVALID_ARG;
   g_events[which][0] = static_cast<hipEvent_t>(start_event);
   g_events[which][1] = static_cast<hipEvent_t>(stop_event);
@@ -118,11 +116,11 @@ extern "C" hbp_status hbp_workspace_bytes(const hbp_attn_desc* desc, int32_t whi
 
 extern "C" hbp_status hbp_profile_capacity(const hbp_attn_desc* desc, int32_t which, int32_t* n_records_out) {
   if (!n_records_out) return HBP_ERR_INVALID_ARG;
-  if (which != HBP_FWD && which != HBP_BWD) return HBP_ERR_INVALID_ARG;
+  if (which != HBP_FWD && which != HBP_BWD && which != HBP_BWD_DQ) return HBP_ERR_INVALID_ARG;
   Strides st;
   const hbp_status s = check_desc(desc, &st);
   if (s != HBP_OK) return s;
-  *n_records_out = kNumCU * (which == HBP_FWD ? fwd_blocks_per_cu(desc->d_qk) : 1);
+  *n_records_out = kNumCU * (which == HBP_BWD ? 1 : 2);
   return HBP_OK;
 }
 
@@ -164,7 +162,7 @@ extern "C" hbp_status hbp_varlen_attn_fwd(const hbp_attn_desc* desc, const void*
 
   hipStream_t hs = static_cast<hipStream_t>(stream);
   if (hbp::launch_zero_counter(p.counter, hs) != 0) return HBP_ERR_DEVICE;
-  const int grid = grid_for((int64_t)n_q_tiles * p.Hq, fwd_blocks_per_cu(desc->d_qk));
+  const int grid = grid_for((int64_t)n_q_tiles * p.Hq, 2);
   if (hbp::launch_fwd(desc->d_qk, desc->d_v, p, grid, hs, g_events[HBP_FWD][0], g_events[HBP_FWD][1]) != 0) return HBP_ERR_DEVICE;
   return HBP_OK;
 }
@@ -172,20 +170,21 @@ extern "C" hbp_status hbp_varlen_attn_fwd(const hbp_attn_desc* desc, const void*
 extern "C" hbp_status hbp_varlen_attn_bwd(const hbp_attn_desc* desc, const void* q, const void* k,
                                           const void* v, const void* o, const float* lse,
                                           const void* d_o, const int32_t* cu_seqlens,
+                                          const hbp_tile* q_tiles, int32_t n_q_tiles,
                                           const hbp_tile* kv_tiles, int32_t n_kv_tiles, void* dq,
                                           void* dk, void* dv, void* workspace,
                                           size_t workspace_bytes, hbp_profile_rec* profile,
-                                          void* stream) {
+                                          hbp_profile_rec* profile_dq, void* stream) {
   Strides st;
   const hbp_status s = check_desc(desc, &st);
   if (s != HBP_OK) return s;
-  if (n_kv_tiles < 0) return HBP_ERR_INVALID_ARG;
+  if (n_kv_tiles < 0 || n_q_tiles < 0) return HBP_ERR_INVALID_ARG;
   const BwdLayout lay = bwd_layout(desc);
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < lay.total)
     return HBP_ERR_WORKSPACE;
   if (desc->total_tokens == 0) return HBP_OK;
   if (!q || !k || !v || !o || !lse || !d_o || !cu_seqlens || !dq || !dk || !dv) return HBP_ERR_INVALID_ARG;
-  if (n_kv_tiles > 0 && !kv_tiles) return HBP_ERR_INVALID_ARG;
+  if ((n_kv_tiles > 0 && !kv_tiles) || (n_q_tiles > 0 && !q_tiles)) return HBP_ERR_INVALID_ARG;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(d_o) ||
       !aligned16(dq) || !aligned16(dk) || !aligned16(dv))
     return HBP_ERR_INVALID_ARG;
@@ -203,11 +202,14 @@ extern "C" hbp_status hbp_varlen_attn_bwd(const hbp_attn_desc* desc, const void*
   p.dv = static_cast<uint16_t*>(dv);
   char* ws = static_cast<char*>(workspace);
   p.counter = reinterpret_cast<int32_t*>(ws);
+  p.counter_dq = reinterpret_cast<int32_t*>(ws + 128);
   p.D = reinterpret_cast<float*>(ws + lay.d_off);
-  p.dq_acc = reinterpret_cast<float*>(ws + lay.dq_off);
   p.cu = cu_seqlens;
   p.tiles = kv_tiles;
   p.n_tiles = n_kv_tiles;
+  p.q_tiles = q_tiles;
+  p.n_q_tiles = n_q_tiles;
+  p.prof_dq = profile_dq;
   p.n_samples = desc->n_samples;
   p.T = desc->total_tokens;
   p.Hq = desc->n_q_heads;
@@ -219,9 +221,10 @@ extern "C" hbp_status hbp_varlen_attn_bwd(const hbp_attn_desc* desc, const void*
   p.scale_log2 = p.scale * 1.4426950408889634f;
   p.prof = profile;
 
-  const int grid = grid_for((int64_t)n_kv_tiles * p.Hkv, 1);
-  if (hbp::launch_bwd(desc->d_qk, desc->d_v, p, grid, static_cast<hipStream_t>(stream), g_events[HBP_BWD][0],
-                      g_events[HBP_BWD][1]) != 0)
+  const int grid_dkdv = grid_for((int64_t)n_kv_tiles * p.Hkv, 1);
+  const int grid_dq = grid_for((int64_t)n_q_tiles * p.Hq, 2);
+  hipEvent_t ev[4] = {g_events[HBP_BWD][0], g_events[HBP_BWD][1], g_events[HBP_BWD_DQ][0], g_events[HBP_BWD_DQ][1]};
+  if (hbp::launch_bwd(desc->d_qk, desc->d_v, p, grid_dq, grid_dkdv, static_cast<hipStream_t>(stream), ev) != 0)
     return HBP_ERR_DEVICE;
   return HBP_OK;
 }

@@ -1,60 +1,273 @@
-// Backward kernels: dQ, dK, dV of causal attention inside each sample of a packed buffer.
+// Backward kernels: dQ, dK, dV of causal attention inside each sample of a packed buffer, gfx950.
 //
-// (1) prepass:  D[h,r] = sum_x dO[r,h,x] O[r,h,x]  and zeroing of the fp32 dQ accumulator.
-// (2) main:     one work item = (key tile of <=128 keys, kv head), served longest cost first by
-//               a persistent grid.  Each of the 4 wavefronts owns 32 keys: their K and V
-//               fragments and the dK^T / dV^T accumulators stay in registers while the
-//               workgroup walks the query blocks (32 rows) at or below the diagonal, for every
-//               query head of the kv head's group.  Per block and wavefront, five MFMA products:
-//                   S  = Q K^T            (accumulator: one key per lane column, queries in-lane)
-//                   dP = dO V^T
-//                   P  = exp2(S*c - LSE*log2e),  dS = P (dP - D)
-//                   dV^T += dO^T P        (P taken straight from the accumulator as B operand)
-//                   dK^T += Q^T dS
-//                   dQ   += dS K          (dS transposed through a per-wave LDS patch)
-//               dQ partial sums go to the fp32 accumulator with hardware float atomics.
-// (3) convert:  dQ = bf16(scale * accumulator).
+// (1) prepass   D[h,r] = sum_x dO[r,h,x] O[r,h,x]; resets the two scheduler counters.
+// (2) dq        query-tile major, same skeleton as the forward: work item = (query tile of <=128
+//               rows, query head); K and V tiles of 64 keys stream through LDS; per 32-key block
+//                   S^T  = K Q^T,  dP^T = V dO^T          (one query per lane column)
+//                   dS^T = exp2(S^T c - LSE log2e) (dP^T - D)
+//                   dQ^T += K^T dS^T                      (K^T by transposing LDS reads)
+// (3) dkdv      key-tile major: work item = (key tile of <=128 keys, kv head); each wavefront keeps
+//               the K and V fragments of its 32 keys and the dK^T / dV^T accumulators in registers
+//               while Q and dO blocks of 64 rows stream through LDS, for every query head of the
+//               group (the GQA reduction happens in the accumulators):
+//                   S  = Q K^T,  dP = dO V^T               (one key per lane column)
+//                   P  = exp2(S c - LSE log2e),  dS = P (dP - D)
+//                   dV^T += dO^T P,  dK^T += Q^T dS        (transposing LDS reads of dO and Q)
+// No atomics: dQ has its own pass (S and dP are recomputed there), so every output is written
+// once and the results are bit-stable from run to run.
 #include "common.hpp"
 
 namespace hbp {
 
-template <int DQK, int DV>
-__global__ __launch_bounds__(kThreads, 1) void bwd_kernel(const BwdParams p) {
-  constexpr int BN = 128, BQ = 32;
-  constexpr int NC = DQK / 16, NCV = DV / 16;   // contraction chunks of S and dP
-  constexpr int NDB = DQK / 32, NEB = DV / 32;  // 32-wide output blocks of dK/dQ and dV
-  constexpr int QP = DQK + 8, OP = DV + 8;      // pitches of the natural Q / dO blocks
-  constexpr int TP = BQ + 8;                    // pitch of the transposed blocks and of dS
-  constexpr int Q_UNITS = (BQ / 4) * (DQK / 2) / kThreads;
-  constexpr int O_UNITS = (BQ / 4) * (DV / 2) / kThreads;
+constexpr float kLog2e = 1.4426950408889634f;
 
-  __shared__ __attribute__((aligned(16))) uint16_t Qs[BQ * QP];
-  __shared__ __attribute__((aligned(16))) uint16_t dOs[BQ * OP];
-  __shared__ __attribute__((aligned(16))) uint16_t Qt[DQK * TP];
-  __shared__ __attribute__((aligned(16))) uint16_t dOt[DV * TP];
-  __shared__ __attribute__((aligned(16))) uint16_t dSs[4 * BQ * TP];
-  __shared__ __attribute__((aligned(16))) float lse_s[BQ];
-  __shared__ __attribute__((aligned(16))) float D_s[BQ];
-  __shared__ int s_item;
+struct ProfAcc {
+  uint32_t n_done = 0;
+  uint64_t t_first = 0, t_last = 0, t_busy = 0, t0 = 0;
+};
+__device__ __forceinline__ void prof_begin(ProfAcc& a, const hbp_profile_rec* prof, int tid) {
+  if (prof && tid == 0) {
+    a.t0 = wall_clock64();
+    if (a.n_done == 0) a.t_first = a.t0;
+  }
+}
+__device__ __forceinline__ void prof_end(ProfAcc& a, const hbp_profile_rec* prof, int tid) {
+  if (prof && tid == 0) {
+    const uint64_t t1 = wall_clock64();
+    a.t_busy += t1 - a.t0;
+    a.t_last = t1;
+    ++a.n_done;
+  }
+}
+__device__ __forceinline__ void prof_write(const ProfAcc& a, hbp_profile_rec* prof, int tid) {
+  if (prof && tid == 0) {
+    hbp_profile_rec r;
+    r.hw_id = hw_id_reg();
+    r.xcc_id = xcc_id_reg();
+    r.n_items = a.n_done;
+    r.reserved = 0;
+    r.first_tick = a.t_first;
+    r.last_tick = a.t_last;
+    r.busy_ticks = a.t_busy;
+    prof[blockIdx.x] = r;
+  }
+}
+
+// ------------------------------------------------------------------------------------- dQ
+template <int DQK, int DV>
+__global__ __launch_bounds__(kThreads, (DQK > 128 ? 1 : 2)) void bwd_dq_kernel(const BwdParams p) {
+  constexpr int BM = 128, BN = 64;
+  constexpr int KRB = DQK * 2, VRB = DV * 2;
+  constexpr int K_TILE = BN * KRB, V_TILE = BN * VRB;
+  constexpr int NC = DQK / 16, NCV = DV / 16, NDB = DQK / 32;
+
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  char* const k_lds = smem;
+  char* const v_lds = smem + 2 * K_TILE;
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
-  constexpr float kLog2e = 1.4426950408889634f;
 
-  uint32_t n_done = 0;
-  uint64_t t_first = 0, t_last = 0, t_busy = 0;
+  int koff[NC], vnoff[NCV], ktoff[2][NDB];
+#pragma unroll
+  for (int c = 0; c < NC; ++c) koff[c] = l32 * KRB + swz<DQK>(2 * c + hh, l32) * 16;
+#pragma unroll
+  for (int c = 0; c < NCV; ++c) vnoff[c] = l32 * VRB + swz<DV>(2 * c + hh, l32) * 16;
+  {
+    const int G = lane >> 4, s = lane & 15;
+    const int k8 = 4 * hh + (s >> 2);
+#pragma unroll
+    for (int r = 0; r < 2; ++r)
+#pragma unroll
+      for (int db = 0; db < NDB; ++db) {
+        const int c = 4 * db + 2 * (G & 1) + ((s & 3) >> 1);
+        ktoff[r][db] = (8 * r + k8) * KRB + swz<DQK>(c, 8 * r + k8) * 16 + (s & 1) * 8;
+      }
+  }
 
+  ProfAcc pa;
   for (;;) {
-    if (tid == 0) s_item = atomicAdd(p.counter, 1);
     __syncthreads();
-    const int item = s_item;
+    if (tid == 0) *(volatile int*)smem = atomicAdd(p.counter_dq, 1);
+    __syncthreads();
+    const int item = *(volatile int*)smem;
+    __syncthreads();
+    if (item >= p.n_q_tiles * p.Hq) break;
+    prof_begin(pa, p.prof_dq, tid);
+
+    const int h = item % p.Hq;
+    const hbp_tile tl = p.q_tiles[item / p.Hq];
+    bool ok = tl.sample >= 0 && tl.sample < p.n_samples;
+    int s0 = 0, s1 = 0;
+    if (ok) {
+      s0 = p.cu[tl.sample];
+      s1 = p.cu[tl.sample + 1];
+      ok = s0 >= 0 && s1 <= p.T && s0 <= tl.row_begin && tl.row_begin < tl.row_end &&
+           tl.row_end <= s1 && tl.row_end - tl.row_begin <= BM;
+    }
+    if (ok) {
+      const int r0 = tl.row_begin, r1 = tl.row_end;
+      const int kh = h / p.g;
+      const int qw0 = r0 - s0 + 32 * wave;
+      const int my_row = r0 + 32 * wave + l32;
+      const bool row_valid = my_row < r1;
+      const bool wave_active = r0 + 32 * wave < r1;
+      const int n_keys = r1 - s0;
+      const int nkt = (n_keys + BN - 1) / BN;
+      const uint16_t* kbase = p.k + (int64_t)s0 * p.k_st + (int64_t)kh * p.k_sh;
+      const uint16_t* vbase = p.v + (int64_t)s0 * p.v_st + (int64_t)kh * p.v_sh;
+
+      auto issue = [&](int kt) {
+        const int k_off = kt * BN;
+        const int valid = n_keys - k_off;
+        async_tile_load<DQK, BN>(kbase + (int64_t)k_off * p.k_st, p.k_st, valid,
+                                 k_lds + (kt & 1) * K_TILE, wave, lane);
+        async_tile_load<DV, BN>(vbase + (int64_t)k_off * p.v_st, p.v_st, valid,
+                                v_lds + (kt & 1) * V_TILE, wave, lane);
+      };
+      issue(0);
+
+      Frag qf[NC], dof[NCV];
+      float lse2 = INFINITY, Dv = 0.f;  // +inf: rows past the tile end get probability 0
+      {
+        const uint16_t* qp = p.q + (int64_t)my_row * p.q_st + (int64_t)h * p.q_sh + 8 * hh;
+        const uint16_t* dop = p.d_o + (int64_t)my_row * p.o_st + (int64_t)h * p.o_sh + 8 * hh;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) qf[c].u = row_valid ? *(const u32x4*)(qp + 16 * c) : u32x4{0, 0, 0, 0};
+#pragma unroll
+        for (int c = 0; c < NCV; ++c) dof[c].u = row_valid ? *(const u32x4*)(dop + 16 * c) : u32x4{0, 0, 0, 0};
+        if (row_valid) {
+          lse2 = p.lse[(int64_t)h * p.T + my_row] * kLog2e;
+          Dv = p.D[(int64_t)h * p.T + my_row];
+        }
+      }
+      f32x16 dqacc[NDB];
+#pragma unroll
+      for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) dqacc[db][i] = 0.f;
+
+      for (int kt = 0; kt < nkt; ++kt) {
+        wait_async_loads();
+        __syncthreads();
+        if (kt + 1 < nkt) issue(kt + 1);
+        const int k_off = kt * BN;
+        if (!wave_active || k_off > qw0 + 31) continue;
+        const char* kt_lds = k_lds + (kt & 1) * K_TILE;
+        const char* vt_lds = v_lds + (kt & 1) * V_TILE;
+        const int q_in = qw0 + l32;
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk) {
+          const int kb = k_off + 32 * blk;
+          if (kb > qw0 + 31) continue;
+          f32x16 sacc, dpacc;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) sacc[i] = 0.f, dpacc[i] = 0.f;
+#pragma unroll
+          for (int c = 0; c < NC; ++c) {
+            Frag a;
+            a.u = *(const u32x4*)(kt_lds + 32 * blk * KRB + koff[c]);
+            sacc = mfma32(a.v, qf[c].v, sacc);
+          }
+#pragma unroll
+          for (int c = 0; c < NCV; ++c) {
+            Frag a;
+            a.u = *(const u32x4*)(vt_lds + 32 * blk * VRB + vnoff[c]);
+            dpacc = mfma32(a.v, dof[c].v, dpacc);
+          }
+          const bool need_mask = kb + 31 > qw0;
+          Frag dsf[2];
+#pragma unroll
+          for (int b = 0; b < 4; ++b) {
+            float ds[4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+              float pr = __builtin_amdgcn_exp2f(sacc[4 * b + v] * p.scale_log2 - lse2);
+              if (need_mask && kb + 8 * b + 4 * hh + v > q_in) pr = 0.f;
+              ds[v] = pr * (dpacc[4 * b + v] - Dv);
+            }
+            dsf[b >> 1].w[2 * (b & 1)] = pack_bf16(ds[0], ds[1]);
+            dsf[b >> 1].w[2 * (b & 1) + 1] = pack_bf16(ds[2], ds[3]);
+          }
+#pragma unroll
+          for (int db = 0; db < NDB; ++db)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+              Frag a;
+              const char* base = kt_lds + (32 * blk + 16 * j) * KRB;
+              a.h[0] = lds_read_tr16(base + ktoff[0][db]);
+              a.h[1] = lds_read_tr16(base + ktoff[1][db]);
+              dqacc[db] = mfma32(a.v, dsf[j].v, dqacc[db]);
+            }
+        }
+      }
+      if (row_valid) {
+        uint16_t* dqp = p.dq + (int64_t)my_row * p.q_st + (int64_t)h * p.q_sh + 4 * hh;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+          for (int b = 0; b < 4; ++b) {
+            u32x2 w = {pack_bf16(dqacc[db][4 * b] * p.scale, dqacc[db][4 * b + 1] * p.scale),
+                       pack_bf16(dqacc[db][4 * b + 2] * p.scale, dqacc[db][4 * b + 3] * p.scale)};
+            *(u32x2*)(dqp + 32 * db + 8 * b) = w;
+          }
+      }
+    }
+    prof_end(pa, p.prof_dq, tid);
+  }
+  prof_write(pa, p.prof_dq, tid);
+}
+
+// ----------------------------------------------------------------------------------- dK, dV
+template <int DQK, int DV>
+__global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p) {
+  constexpr int BN = 128, BQ = 64;
+  constexpr int QRB = DQK * 2, ORB = DV * 2;
+  constexpr int Q_TILE = BQ * QRB, O_TILE = BQ * ORB;
+  constexpr int NC = DQK / 16, NCV = DV / 16, NDB = DQK / 32, NEB = DV / 32;
+
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  // [Q buf0][Q buf1][dO buf0][dO buf1][lse buf0|buf1][D buf0|buf1]
+  char* const q_lds = smem;
+  char* const o_lds = smem + 2 * Q_TILE;
+  float* const lse_lds = (float*)(smem + 2 * Q_TILE + 2 * O_TILE);
+  float* const d_lds = lse_lds + 2 * BQ;
+
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
+
+  int qoff[NC], dooff[NCV], qtoff[2][NDB], dotoff[2][NEB];
+#pragma unroll
+  for (int c = 0; c < NC; ++c) qoff[c] = l32 * QRB + swz<DQK>(2 * c + hh, l32) * 16;
+#pragma unroll
+  for (int c = 0; c < NCV; ++c) dooff[c] = l32 * ORB + swz<DV>(2 * c + hh, l32) * 16;
+  {
+    const int G = lane >> 4, s = lane & 15;
+    const int k8 = 4 * hh + (s >> 2);
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+#pragma unroll
+      for (int db = 0; db < NDB; ++db) {
+        const int c = 4 * db + 2 * (G & 1) + ((s & 3) >> 1);
+        qtoff[r][db] = (8 * r + k8) * QRB + swz<DQK>(c, 8 * r + k8) * 16 + (s & 1) * 8;
+      }
+#pragma unroll
+      for (int eb = 0; eb < NEB; ++eb) {
+        const int c = 4 * eb + 2 * (G & 1) + ((s & 3) >> 1);
+        dotoff[r][eb] = (8 * r + k8) * ORB + swz<DV>(c, 8 * r + k8) * 16 + (s & 1) * 8;
+      }
+    }
+  }
+
+  ProfAcc pa;
+  for (;;) {
+    __syncthreads();
+    if (tid == 0) *(volatile int*)smem = atomicAdd(p.counter, 1);
+    __syncthreads();
+    const int item = *(volatile int*)smem;
     __syncthreads();
     if (item >= p.n_tiles * p.Hkv) break;
-    uint64_t t0 = 0;
-    if (p.prof && tid == 0) {
-      t0 = wall_clock64();
-      if (n_done == 0) t_first = t0;
-    }
+    prof_begin(pa, p.prof, tid);
 
     const int kh = item % p.Hkv;
     const hbp_tile tl = p.tiles[item / p.Hkv];
@@ -68,14 +281,38 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_kernel(const BwdParams p) {
     }
     if (ok) {
       const int s_len = s1 - s0;
-      const int k0_in = tl.row_begin - s0;             // in-sample index of the tile's first key
-      const int kw0_in = k0_in + 32 * wave;            // ... of this wave's first key
-      const int my_key = tl.row_begin + 32 * wave + l32;  // absolute row of this lane's key column
+      const int k0_in = tl.row_begin - s0;
+      const int kw0_in = k0_in + 32 * wave;
+      const int my_key = tl.row_begin + 32 * wave + l32;
       const bool key_valid = my_key < tl.row_end;
       const bool wave_active = tl.row_begin + 32 * wave < tl.row_end;
+      const int key_in = kw0_in + l32;
 
-      // register-resident operands of this wave's 32 keys
-      Frag knat[NC], vnat[NCV], ktr[NDB][2];
+      const int qb_start = (k0_in / BQ) * BQ;
+      const int nqb = (s_len - qb_start + BQ - 1) / BQ;
+      const int n_steps = nqb * p.g;
+
+      auto issue = [&](int step) {
+        const int hq = kh * p.g + step / nqb;
+        const int qb = qb_start + (step % nqb) * BQ;
+        const int valid = s_len - qb;  // >= 1
+        const int buf = step & 1;
+        async_tile_load<DQK, BQ>(p.q + (int64_t)(s0 + qb) * p.q_st + (int64_t)hq * p.q_sh, p.q_st, valid,
+                                 q_lds + buf * Q_TILE, wave, lane);
+        async_tile_load<DV, BQ>(p.d_o + (int64_t)(s0 + qb) * p.o_st + (int64_t)hq * p.o_sh, p.o_st, valid,
+                                o_lds + buf * O_TILE, wave, lane);
+        if (wave < 2) {
+          const int row = lane < valid ? lane : valid - 1;
+          const float* src = (wave == 0 ? p.lse : p.D) + (int64_t)hq * p.T + s0 + qb + row;
+          float* dst = (wave == 0 ? lse_lds : d_lds) + buf * BQ;
+          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                           (__attribute__((address_space(3))) void*)dst, 4, 0, 0);
+        }
+      };
+      if (n_steps > 0) issue(0);
+
+      // register-resident B operands of this wave's 32 keys: lane column = key l32
+      Frag knat[NC], vnat[NCV];
       {
         const uint16_t* kp = p.k + (int64_t)my_key * p.k_st + (int64_t)kh * p.k_sh + 8 * hh;
         const uint16_t* vp = p.v + (int64_t)my_key * p.v_st + (int64_t)kh * p.v_sh + 8 * hh;
@@ -83,21 +320,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_kernel(const BwdParams p) {
         for (int c = 0; c < NC; ++c) knat[c].u = key_valid ? *(const u32x4*)(kp + 16 * c) : u32x4{0, 0, 0, 0};
 #pragma unroll
         for (int c = 0; c < NCV; ++c) vnat[c].u = key_valid ? *(const u32x4*)(vp + 16 * c) : u32x4{0, 0, 0, 0};
-        // B operand of dQ = dS K: lane column d = 32db + l32, contraction rows = keys 16j+8hh+i
-#pragma unroll
-        for (int db = 0; db < NDB; ++db)
-#pragma unroll
-          for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int w = 0; w < 4; ++w) {
-              const int key_a = tl.row_begin + 32 * wave + 16 * j + 8 * hh + 2 * w;
-              const uint16_t* ka = p.k + (int64_t)key_a * p.k_st + (int64_t)kh * p.k_sh + 32 * db + l32;
-              const uint32_t lo = key_a < tl.row_end ? (uint32_t)ka[0] : 0u;
-              const uint32_t hi = key_a + 1 < tl.row_end ? (uint32_t)ka[p.k_st] : 0u;
-              ktr[db][j].w[w] = lo | (hi << 16);
-            }
       }
-
       f32x16 dkt[NDB], dvt[NEB];
 #pragma unroll
       for (int db = 0; db < NDB; ++db)
@@ -108,181 +331,82 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_kernel(const BwdParams p) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) dvt[eb][i] = 0.f;
 
-      const int qb_start = (k0_in / BQ) * BQ;
-      const int nqb = (s_len - qb_start + BQ - 1) / BQ;  // query blocks per head
-      const int n_steps = nqb * p.g;
-
-      uint32_t qreg[Q_UNITS][4], oreg[O_UNITS][4];
-      float lse_reg = 0.f, D_reg = 0.f;
-
-      auto load_block = [&](int step) {
-        const int hq = kh * p.g + step / nqb;
-        const int qb = qb_start + (step % nqb) * BQ;
-        const uint16_t* qb_ptr = p.q + (int64_t)(s0 + qb) * p.q_st + (int64_t)hq * p.q_sh;
-        const uint16_t* ob_ptr = p.d_o + (int64_t)(s0 + qb) * p.o_st + (int64_t)hq * p.o_sh;
-#pragma unroll
-        for (int i = 0; i < Q_UNITS; ++i) {
-          const int u = tid + kThreads * i;
-          const int cp = u % (DQK / 2), rg = u / (DQK / 2);
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const int row = 4 * rg + j;
-            qreg[i][j] = qb + row < s_len ? *(const uint32_t*)(qb_ptr + (int64_t)row * p.q_st + 2 * cp) : 0u;
-          }
-        }
-#pragma unroll
-        for (int i = 0; i < O_UNITS; ++i) {
-          const int u = tid + kThreads * i;
-          const int cp = u % (DV / 2), rg = u / (DV / 2);
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const int row = 4 * rg + j;
-            oreg[i][j] = qb + row < s_len ? *(const uint32_t*)(ob_ptr + (int64_t)row * p.o_st + 2 * cp) : 0u;
-          }
-        }
-        if (tid < BQ) {
-          const bool v = qb + tid < s_len;
-          // +inf for rows past the sample end makes their probabilities exactly zero
-          lse_reg = v ? p.lse[(int64_t)hq * p.T + s0 + qb + tid] * kLog2e : INFINITY;
-          D_reg = v ? p.D[(int64_t)hq * p.T + s0 + qb + tid] : 0.f;
-        }
-      };
-      auto store_block = [&]() {
-#pragma unroll
-        for (int i = 0; i < Q_UNITS; ++i) {
-          const int u = tid + kThreads * i;
-          const int cp = u % (DQK / 2), rg = u / (DQK / 2);
-          const int pos = 16 * (rg >> 2) + tslot(4 * (rg & 3));
-          const uint32_t a0 = qreg[i][0], a1 = qreg[i][1], a2 = qreg[i][2], a3 = qreg[i][3];
-#pragma unroll
-          for (int j = 0; j < 4; ++j) *(uint32_t*)&Qs[(4 * rg + j) * QP + 2 * cp] = qreg[i][j];
-          u32x2 lo = {(a0 & 0xffffu) | (a1 << 16), (a2 & 0xffffu) | (a3 << 16)};
-          u32x2 hi = {(a0 >> 16) | (a1 & 0xffff0000u), (a2 >> 16) | (a3 & 0xffff0000u)};
-          *(u32x2*)&Qt[(2 * cp) * TP + pos] = lo;
-          *(u32x2*)&Qt[(2 * cp + 1) * TP + pos] = hi;
-        }
-#pragma unroll
-        for (int i = 0; i < O_UNITS; ++i) {
-          const int u = tid + kThreads * i;
-          const int cp = u % (DV / 2), rg = u / (DV / 2);
-          const int pos = 16 * (rg >> 2) + tslot(4 * (rg & 3));
-          const uint32_t a0 = oreg[i][0], a1 = oreg[i][1], a2 = oreg[i][2], a3 = oreg[i][3];
-#pragma unroll
-          for (int j = 0; j < 4; ++j) *(uint32_t*)&dOs[(4 * rg + j) * OP + 2 * cp] = oreg[i][j];
-          u32x2 lo = {(a0 & 0xffffu) | (a1 << 16), (a2 & 0xffffu) | (a3 << 16)};
-          u32x2 hi = {(a0 >> 16) | (a1 & 0xffff0000u), (a2 >> 16) | (a3 & 0xffff0000u)};
-          *(u32x2*)&dOt[(2 * cp) * TP + pos] = lo;
-          *(u32x2*)&dOt[(2 * cp + 1) * TP + pos] = hi;
-        }
-        if (tid < BQ) {
-          lse_s[tid] = lse_reg;
-          D_s[tid] = D_reg;
-        }
-      };
-
-      uint16_t* my_dS = dSs + wave * BQ * TP;
-
-      if (n_steps > 0) load_block(0);
       for (int step = 0; step < n_steps; ++step) {
+        wait_async_loads();
         __syncthreads();
-        store_block();
-        __syncthreads();
-        const int hq = kh * p.g + step / nqb;
+        if (step + 1 < n_steps) issue(step + 1);
         const int qb = qb_start + (step % nqb) * BQ;
-        if (step + 1 < n_steps) load_block(step + 1);
         if (!wave_active || qb + BQ - 1 < kw0_in) continue;  // block lies above this wave's keys
-
-        f32x16 sacc, dpacc;
+        const int buf = step & 1;
+        const char* qt = q_lds + buf * Q_TILE;
+        const char* ot = o_lds + buf * O_TILE;
+        const float* lse_b = lse_lds + buf * BQ;
+        const float* d_b = d_lds + buf * BQ;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) sacc[i] = 0.f, dpacc[i] = 0.f;
+        for (int sub = 0; sub < 2; ++sub) {
+          const int q0 = qb + 32 * sub;  // in-sample index of the sub-block's first query
+          if (q0 + 31 < kw0_in || q0 >= s_len) continue;
+          f32x16 sacc, dpacc;
 #pragma unroll
-        for (int c = 0; c < NC; ++c) {
-          Frag a;
-          a.u = *(const u32x4*)&Qs[l32 * QP + 16 * c + 8 * hh];
-          sacc = mfma32(a.v, knat[c].v, sacc);
-        }
+          for (int i = 0; i < 16; ++i) sacc[i] = 0.f, dpacc[i] = 0.f;
 #pragma unroll
-        for (int c = 0; c < NCV; ++c) {
-          Frag a;
-          a.u = *(const u32x4*)&dOs[l32 * OP + 16 * c + 8 * hh];
-          dpacc = mfma32(a.v, vnat[c].v, dpacc);
-        }
-        // accumulator element 4b+v <-> query row qb + 8b + 4hh + v, key column kw0_in + l32
-        const bool need_mask = kw0_in + 31 > qb;
-        const int key_in = kw0_in + l32;
-        Frag pb[2], dsb[2];
-        float dsv[16];
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-          const f32x4 l4 = *(const f32x4*)&lse_s[8 * b + 4 * hh];
-          const f32x4 d4 = *(const f32x4*)&D_s[8 * b + 4 * hh];
-          float pv[4];
-#pragma unroll
-          for (int v = 0; v < 4; ++v) {
-            float pr = __builtin_amdgcn_exp2f(sacc[4 * b + v] * p.scale_log2 - l4[v]);
-            if (need_mask && key_in > qb + 8 * b + 4 * hh + v) pr = 0.f;
-            pv[v] = pr;
-            dsv[4 * b + v] = pr * (dpacc[4 * b + v] - d4[v]);
-          }
-          pb[b >> 1].w[2 * (b & 1)] = pack_bf16(pv[0], pv[1]);
-          pb[b >> 1].w[2 * (b & 1) + 1] = pack_bf16(pv[2], pv[3]);
-          dsb[b >> 1].w[2 * (b & 1)] = pack_bf16(dsv[4 * b], dsv[4 * b + 1]);
-          dsb[b >> 1].w[2 * (b & 1) + 1] = pack_bf16(dsv[4 * b + 2], dsv[4 * b + 3]);
-        }
-        // dV^T += dO^T P ; dK^T += Q^T dS  (contraction over the 32 query rows, two chunks of 16)
-#pragma unroll
-        for (int eb = 0; eb < NEB; ++eb)
-#pragma unroll
-          for (int j = 0; j < 2; ++j) {
+          for (int c = 0; c < NC; ++c) {
             Frag a;
-            a.u = *(const u32x4*)&dOt[(32 * eb + l32) * TP + 16 * j + 8 * hh];
-            dvt[eb] = mfma32(a.v, pb[j].v, dvt[eb]);
+            a.u = *(const u32x4*)(qt + 32 * sub * QRB + qoff[c]);
+            sacc = mfma32(a.v, knat[c].v, sacc);
           }
 #pragma unroll
-        for (int db = 0; db < NDB; ++db)
-#pragma unroll
-          for (int j = 0; j < 2; ++j) {
+          for (int c = 0; c < NCV; ++c) {
             Frag a;
-            a.u = *(const u32x4*)&Qt[(32 * db + l32) * TP + 16 * j + 8 * hh];
-            dkt[db] = mfma32(a.v, dsb[j].v, dkt[db]);
+            a.u = *(const u32x4*)(ot + 32 * sub * ORB + dooff[c]);
+            dpacc = mfma32(a.v, vnat[c].v, dpacc);
           }
-        // transpose dS through this wave's LDS patch: [query][key]
+          // accumulator element 4b+v <-> query q0 + 8b + 4hh + v, key column key_in
+          const bool need_mask = kw0_in + 31 > q0 || q0 + 31 >= s_len;
+          Frag pb[2], dsb[2];
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
+          for (int b = 0; b < 4; ++b) {
+            const f32x4 l4 = *(const f32x4*)&lse_b[32 * sub + 8 * b + 4 * hh];
+            const f32x4 d4 = *(const f32x4*)&d_b[32 * sub + 8 * b + 4 * hh];
+            float pv[4], ds[4];
 #pragma unroll
-          for (int v = 0; v < 4; v += 2) {
-            const uint32_t w = dsb[b >> 1].w[2 * (b & 1) + (v >> 1)];
-            my_dS[(8 * b + 4 * hh + v) * TP + l32] = (uint16_t)(w & 0xffffu);
-            my_dS[(8 * b + 4 * hh + v + 1) * TP + l32] = (uint16_t)(w >> 16);
+            for (int v = 0; v < 4; ++v) {
+              float pr = __builtin_amdgcn_exp2f(sacc[4 * b + v] * p.scale_log2 - l4[v] * kLog2e);
+              if (need_mask) {
+                const int q_in = q0 + 8 * b + 4 * hh + v;
+                if (key_in > q_in || q_in >= s_len) pr = 0.f;
+              }
+              pv[v] = pr;
+              ds[v] = pr * (dpacc[4 * b + v] - d4[v]);
+            }
+            pb[b >> 1].w[2 * (b & 1)] = pack_bf16(pv[0], pv[1]);
+            pb[b >> 1].w[2 * (b & 1) + 1] = pack_bf16(pv[2], pv[3]);
+            dsb[b >> 1].w[2 * (b & 1)] = pack_bf16(ds[0], ds[1]);
+            dsb[b >> 1].w[2 * (b & 1) + 1] = pack_bf16(ds[2], ds[3]);
           }
+#pragma unroll
+          for (int eb = 0; eb < NEB; ++eb)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+              Frag a;
+              const char* base = ot + (32 * sub + 16 * j) * ORB;
+              a.h[0] = lds_read_tr16(base + dotoff[0][eb]);
+              a.h[1] = lds_read_tr16(base + dotoff[1][eb]);
+              dvt[eb] = mfma32(a.v, pb[j].v, dvt[eb]);
+            }
+#pragma unroll
+          for (int db = 0; db < NDB; ++db)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+              Frag a;
+              const char* base = qt + (32 * sub + 16 * j) * QRB;
+              a.h[0] = lds_read_tr16(base + qtoff[0][db]);
+              a.h[1] = lds_read_tr16(base + qtoff[1][db]);
+              dkt[db] = mfma32(a.v, dsb[j].v, dkt[db]);
+            }
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        // dQ[q, d] += sum_key dS[q,key] K[key,d]
-        float* dq_row = p.dq_acc + ((int64_t)(s0 + qb) * p.Hq + hq) * DQK + l32;
-#pragma unroll
-        for (int db = 0; db < NDB; ++db) {
-          f32x16 dq;
-#pragma unroll
-          for (int i = 0; i < 16; ++i) dq[i] = 0.f;
-#pragma unroll
-          for (int j = 0; j < 2; ++j) {
-            Frag a;
-            a.u = *(const u32x4*)&my_dS[l32 * TP + 16 * j + 8 * hh];
-            dq = mfma32(a.v, ktr[db][j].v, dq);
-          }
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const int row = 8 * (i >> 2) + 4 * hh + (i & 3);
-            if (qb + row < s_len)
-              unsafeAtomicAdd(dq_row + (int64_t)row * p.Hq * DQK + 32 * db, dq[i]);
-          }
-        }
-        __builtin_amdgcn_wave_barrier();
       }
 
-      // store dK = scale * dK^T^T, dV = dV^T^T : lane column = key, 4 consecutive dims per element group
       if (key_valid) {
         uint16_t* dkp = p.dk + (int64_t)my_key * p.k_st + (int64_t)kh * p.k_sh + 4 * hh;
         uint16_t* dvp = p.dv + (int64_t)my_key * p.v_st + (int64_t)kh * p.v_sh + 4 * hh;
@@ -304,32 +428,19 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_kernel(const BwdParams p) {
           }
       }
     }
-    if (p.prof && tid == 0) {
-      const uint64_t t1 = wall_clock64();
-      t_busy += t1 - t0;
-      t_last = t1;
-      ++n_done;
-    }
+    prof_end(pa, p.prof, tid);
   }
-  if (p.prof && tid == 0) {
-    hbp_profile_rec r;
-    r.hw_id = hw_id_reg();
-    r.xcc_id = xcc_id_reg();
-    r.n_items = n_done;
-    r.reserved = 0;
-    r.first_tick = t_first;
-    r.last_tick = t_last;
-    r.busy_ticks = t_busy;
-    p.prof[blockIdx.x] = r;
-  }
+  prof_write(pa, p.prof, tid);
 }
 
-// D[h,r] = sum_x dO[r,h,x] O[r,h,x]; zero the fp32 dQ accumulator row (r,h); reset the counter.
-template <int DQK, int DV>
+// D[h,r] = sum_x dO[r,h,x] O[r,h,x]; resets both scheduler counters.
+template <int DV>
 __global__ __launch_bounds__(kThreads) void bwd_prepass_kernel(const BwdParams p) {
-  constexpr int LPR = DV / 8;          // lanes per (row, head): 16 bytes of O and dO each
-  constexpr int ZPL = DQK / LPR;       // accumulator floats zeroed per lane
-  if (blockIdx.x == 0 && threadIdx.x == 0) *p.counter = 0;
+  constexpr int LPR = DV / 8;  // lanes per (row, head): 16 bytes of O and dO each
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    *p.counter = 0;
+    *p.counter_dq = 0;
+  }
   const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   const int64_t rh = gid / LPR;
   const int part = (int)(gid % LPR);
@@ -343,9 +454,6 @@ __global__ __launch_bounds__(kThreads) void bwd_prepass_kernel(const BwdParams p
     const u32x4 b = *(const u32x4*)(p.d_o + off);
 #pragma unroll
     for (int i = 0; i < 4; ++i) acc += bf16_lo(a[i]) * bf16_lo(b[i]) + bf16_hi(a[i]) * bf16_hi(b[i]);
-    float* z = p.dq_acc + rh * DQK + (int64_t)part * ZPL;
-#pragma unroll
-    for (int i = 0; i < ZPL; i += 4) *(f32x4*)(z + i) = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 #pragma unroll
   for (int m = LPR / 2; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
@@ -356,52 +464,47 @@ __global__ __launch_bounds__(kThreads) void bwd_prepass_kernel(const BwdParams p
   }
 }
 
-// dQ = bf16(scale * accumulator)
-template <int DQK>
-__global__ __launch_bounds__(kThreads) void bwd_convert_kernel(const BwdParams p) {
-  constexpr int CPR = DQK / 8;  // 8-element chunks per (row, head)
-  const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-  const int64_t rh = gid / CPR;
-  const int part = (int)(gid % CPR);
-  if (rh >= (int64_t)p.T * p.Hq) return;
-  const int64_t r = rh / p.Hq;
-  const int h = (int)(rh % p.Hq);
-  const float* a = p.dq_acc + rh * DQK + 8 * part;
-  const f32x4 x = *(const f32x4*)a, y = *(const f32x4*)(a + 4);
-  u32x4 w = {pack_bf16(x[0] * p.scale, x[1] * p.scale), pack_bf16(x[2] * p.scale, x[3] * p.scale),
-             pack_bf16(y[0] * p.scale, y[1] * p.scale), pack_bf16(y[2] * p.scale, y[3] * p.scale)};
-  *(u32x4*)(p.dq + r * p.q_st + (int64_t)h * p.q_sh + 8 * part) = w;
-}
-
 template <int DQK, int DV>
-static int launch_bwd_t(const BwdParams& p, int grid, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
-  const int64_t rh = (int64_t)p.T * p.Hq;
-  const int64_t pre_threads = rh * (DV / 8);
-  const int64_t cvt_threads = rh * (DQK / 8);
+static int launch_bwd_t(const BwdParams& p, int grid_dq, int grid_dkdv, hipStream_t s, hipEvent_t* ev) {
+  constexpr int lds_dq = 2 * 64 * (DQK * 2 + DV * 2);
+  constexpr int lds_dkdv = 2 * 64 * (DQK * 2 + DV * 2) + 4 * 64 * (int)sizeof(float);
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)bwd_dq_kernel<DQK, DV>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_dq);
+    if (e != hipSuccess) return (int)e;
+    e = hipFuncSetAttribute((const void*)bwd_dkdv_kernel<DQK, DV>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_dkdv);
+    if (e != hipSuccess) return (int)e;
+    attr_set = true;
+  }
+  const int64_t pre_threads = (int64_t)p.T * p.Hq * (DV / 8);
   const unsigned pre_grid = (unsigned)((pre_threads + kThreads - 1) / kThreads);
-  const unsigned cvt_grid = (unsigned)((cvt_threads + kThreads - 1) / kThreads);
-  hipLaunchKernelGGL((bwd_prepass_kernel<DQK, DV>), dim3(pre_grid ? pre_grid : 1), dim3(kThreads), 0, s, p);
+  hipLaunchKernelGGL((bwd_prepass_kernel<DV>), dim3(pre_grid ? pre_grid : 1), dim3(kThreads), 0, s, p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return (int)e;
-  if (grid > 0) {
-    if (ev0 && hipEventRecord(ev0, s) != hipSuccess) return (int)hipErrorInvalidValue;
-    hipLaunchKernelGGL((bwd_kernel<DQK, DV>), dim3(grid), dim3(kThreads), 0, s, p);
+  if (grid_dkdv > 0) {
+    if (ev[0] && hipEventRecord(ev[0], s) != hipSuccess) return (int)hipErrorInvalidValue;
+    hipLaunchKernelGGL((bwd_dkdv_kernel<DQK, DV>), dim3(grid_dkdv), dim3(kThreads), lds_dkdv, s, p);
     e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
-    if (ev1 && hipEventRecord(ev1, s) != hipSuccess) return (int)hipErrorInvalidValue;
+    if (ev[1] && hipEventRecord(ev[1], s) != hipSuccess) return (int)hipErrorInvalidValue;
   }
-  if (cvt_grid > 0) {
-    hipLaunchKernelGGL((bwd_convert_kernel<DQK>), dim3(cvt_grid), dim3(kThreads), 0, s, p);
+  if (grid_dq > 0) {
+    if (ev[2] && hipEventRecord(ev[2], s) != hipSuccess) return (int)hipErrorInvalidValue;
+    hipLaunchKernelGGL((bwd_dq_kernel<DQK, DV>), dim3(grid_dq), dim3(kThreads), lds_dq, s, p);
     e = hipGetLastError();
+    if (e != hipSuccess) return (int)e;
+    if (ev[3] && hipEventRecord(ev[3], s) != hipSuccess) return (int)hipErrorInvalidValue;
   }
   return (int)e;
 }
 
-int launch_bwd(int d_qk, int d_v, const BwdParams& p, int grid, hipStream_t s, hipEvent_t ev0,
-               hipEvent_t ev1) {
-  if (d_qk == 64 && d_v == 64) return launch_bwd_t<64, 64>(p, grid, s, ev0, ev1);
-  if (d_qk == 128 && d_v == 128) return launch_bwd_t<128, 128>(p, grid, s, ev0, ev1);
-  if (d_qk == 192 && d_v == 128) return launch_bwd_t<192, 128>(p, grid, s, ev0, ev1);
+int launch_bwd(int d_qk, int d_v, const BwdParams& p, int grid_dq, int grid_dkdv, hipStream_t s,
+               hipEvent_t* ev) {
+  if (d_qk == 64 && d_v == 64) return launch_bwd_t<64, 64>(p, grid_dq, grid_dkdv, s, ev);
+  if (d_qk == 128 && d_v == 128) return launch_bwd_t<128, 128>(p, grid_dq, grid_dkdv, s, ev);
+  if (d_qk == 192 && d_v == 128) return launch_bwd_t<192, 128>(p, grid_dq, grid_dkdv, s, ev);
   return (int)hipErrorInvalidValue;
 }
 

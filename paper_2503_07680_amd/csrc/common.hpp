@@ -135,21 +135,22 @@ struct BwdParams {
   const uint16_t *q, *k, *v, *o, *d_o;
   const float* lse;
   uint16_t *dq, *dk, *dv;
-  float* D;       // [Hq,T]
-  float* dq_acc;  // [T,Hq,d_qk] fp32
+  float* D;  // [Hq,T]
   const int32_t* cu;
-  const hbp_tile* tiles;
-  int32_t n_tiles, n_samples, T, Hq, Hkv, g;
+  const hbp_tile* tiles;    // key tiles (dK/dV kernel)
+  const hbp_tile* q_tiles;  // query tiles (dQ kernel)
+  int32_t n_tiles, n_q_tiles, n_samples, T, Hq, Hkv, g;
   int64_t q_st, q_sh, k_st, k_sh, v_st, v_sh, o_st, o_sh;
   float scale, scale_log2;
-  int32_t* counter;
-  hbp_profile_rec* prof;
+  int32_t *counter, *counter_dq;
+  hbp_profile_rec *prof, *prof_dq;
 };
 
 // launchers implemented in the .hip files; return hipError_t as int
 // ev0/ev1: optional events recorded around the persistent main kernel
 int launch_fwd(int d_qk, int d_v, const FwdParams& p, int grid, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
-int launch_bwd(int d_qk, int d_v, const BwdParams& p, int grid, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
+// ev: {dkdv start, dkdv stop, dq start, dq stop}, entries may be null
+int launch_bwd(int d_qk, int d_v, const BwdParams& p, int grid_dq, int grid_dkdv, hipStream_t s, hipEvent_t* ev);
 int launch_zero_counter(int32_t* counter, hipStream_t s);
 
 }  // namespace hbp

@@ -41,12 +41,14 @@ class PackedAttention:
         self.kv_tiles_dev = torch.from_numpy(self.kv_tiles).to(dev)
         self.ws_fwd = torch.empty(B.hbp_workspace_bytes(self.desc, B.HBP_FWD), dtype=torch.uint8, device=dev)
         self.ws_bwd = None
-        self.prof_fwd = self.prof_bwd = None
+        self.prof_fwd = self.prof_bwd = self.prof_dq = None
         if with_profile:
             n = B.hbp_profile_capacity(self.desc, B.HBP_FWD)
             self.prof_fwd = torch.zeros(n * B.PROFILE_DTYPE.itemsize, dtype=torch.uint8, device=dev)
             n = B.hbp_profile_capacity(self.desc, B.HBP_BWD)
             self.prof_bwd = torch.zeros(n * B.PROFILE_DTYPE.itemsize, dtype=torch.uint8, device=dev)
+            n = B.hbp_profile_capacity(self.desc, B.HBP_BWD_DQ)
+            self.prof_dq = torch.zeros(n * B.PROFILE_DTYPE.itemsize, dtype=torch.uint8, device=dev)
         T = max(self.T, 1)
         bf = torch.bfloat16
         self.o = torch.zeros((T, n_q_heads, d_v), dtype=bf, device=dev)
@@ -79,13 +81,15 @@ class PackedAttention:
 
     def backward(self, q, k, v, d_o, profile: bool = False):
         self.alloc_backward()
-        B.hbp_varlen_attn_bwd(self.desc, q, k, v, self.o, self.lse, d_o, self.cu_dev, self.kv_tiles_dev,
-                              len(self.kv_tiles), self.dq, self.dk, self.dv, self.ws_bwd,
-                              self.prof_bwd if profile else None, self._stream())
+        B.hbp_varlen_attn_bwd(self.desc, q, k, v, self.o, self.lse, d_o, self.cu_dev,
+                              self.q_tiles_dev, len(self.q_tiles), self.kv_tiles_dev, len(self.kv_tiles),
+                              self.dq, self.dk, self.dv, self.ws_bwd,
+                              self.prof_bwd if profile else None, self.prof_dq if profile else None,
+                              self._stream())
         return self.dq, self.dk, self.dv
 
     def profile_records(self, which: int) -> np.ndarray:
-        buf = self.prof_fwd if which == B.HBP_FWD else self.prof_bwd
+        buf = {B.HBP_FWD: self.prof_fwd, B.HBP_BWD: self.prof_bwd, B.HBP_BWD_DQ: self.prof_dq}[which]
         return np.frombuffer(buf.cpu().numpy().tobytes(), dtype=B.PROFILE_DTYPE)
 
 
