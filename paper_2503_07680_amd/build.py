@@ -14,7 +14,7 @@ LIB = os.path.join(PKG, "libhbp.so")
 OBJ_DIR = os.path.join(PKG, "_build")
 SOURCES = ["api.hip", "fwd.hip", "bwd.hip", "plan.cpp"]
 
-HIP_FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-munsafe-fp-atomics",
+HIP_FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-munsafe-fp-atomics", "-Wno-inline-asm",
              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
              "-I", INCLUDE, "-I", CSRC]
 

@@ -66,7 +66,8 @@ __global__ __launch_bounds__(kThreads, (DQK > 128 ? 1 : 2)) void bwd_dq_kernel(c
   char* const v_lds = smem + 2 * K_TILE;
 
   const int tid = threadIdx.x;
-  const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
 
   int koff[NC], vnoff[NCV], ktoff[2][NDB];
 #pragma unroll
@@ -85,12 +86,18 @@ __global__ __launch_bounds__(kThreads, (DQK > 128 ? 1 : 2)) void bwd_dq_kernel(c
       }
   }
 
+  TileLoader<DQK, BN> k_loader;
+  TileLoader<DV, BN> v_loader;
+  k_loader.init(wave, lane);
+  v_loader.init(wave, lane);
+  const uint32_t k_stride_b = (uint32_t)p.k_st * 2, v_stride_b = (uint32_t)p.v_st * 2;
+
   ProfAcc pa;
   for (;;) {
     __syncthreads();
     if (tid == 0) *(volatile int*)smem = atomicAdd(p.counter_dq, 1);
     __syncthreads();
-    const int item = *(volatile int*)smem;
+    const int item = __builtin_amdgcn_readfirstlane(*(volatile int*)smem);
     __syncthreads();
     if (item >= p.n_q_tiles * p.Hq) break;
     prof_begin(pa, p.prof_dq, tid);
@@ -120,10 +127,8 @@ __global__ __launch_bounds__(kThreads, (DQK > 128 ? 1 : 2)) void bwd_dq_kernel(c
       auto issue = [&](int kt) {
         const int k_off = kt * BN;
         const int valid = n_keys - k_off;
-        async_tile_load<DQK, BN>(kbase + (int64_t)k_off * p.k_st, p.k_st, valid,
-                                 k_lds + (kt & 1) * K_TILE, wave, lane);
-        async_tile_load<DV, BN>(vbase + (int64_t)k_off * p.v_st, p.v_st, valid,
-                                v_lds + (kt & 1) * V_TILE, wave, lane);
+        k_loader.issue(kbase + (int64_t)k_off * p.k_st, k_stride_b, valid, k_lds + (kt & 1) * K_TILE, wave);
+        v_loader.issue(vbase + (int64_t)k_off * p.v_st, v_stride_b, valid, v_lds + (kt & 1) * V_TILE, wave);
       };
       issue(0);
 
@@ -163,18 +168,31 @@ __global__ __launch_bounds__(kThreads, (DQK > 128 ? 1 : 2)) void bwd_dq_kernel(c
           f32x16 sacc, dpacc;
 #pragma unroll
           for (int i = 0; i < 16; ++i) sacc[i] = 0.f, dpacc[i] = 0.f;
-#pragma unroll
-          for (int c = 0; c < NC; ++c) {
-            Frag a;
-            a.u = *(const u32x4*)(kt_lds + 32 * blk * KRB + koff[c]);
-            sacc = mfma32(a.v, qf[c].v, sacc);
+          {
+            // S^T = K Q^T (steps 0..NC-1) and dP^T = V dO^T (steps NC..NC+NCV-1), one read pipeline
+            auto load = [&](int i) {
+              Frag a;
+              if (i < NC) a.u = *(const u32x4*)(kt_lds + 32 * blk * KRB + koff[i]);
+              else a.u = *(const u32x4*)(vt_lds + 32 * blk * VRB + vnoff[i - NC]);
+              return a;
+            };
+            LdsChain<NC + NCV, 4> ch;
+            ch.prefill(load);
+            ch.run(load, [&](int i, const Frag& a) {
+              if (i < NC) sacc = mfma32(a.v, qf[i].v, sacc);
+              else dpacc = mfma32(a.v, dof[i - NC].v, dpacc);
+            });
           }
-#pragma unroll
-          for (int c = 0; c < NCV; ++c) {
+          auto load_kt = [&](int i) {  // step (j, db), db fastest
+            const int db = i % NDB, j = i / NDB;
+            const char* base = kt_lds + (32 * blk + 16 * j) * KRB;
             Frag a;
-            a.u = *(const u32x4*)(vt_lds + 32 * blk * VRB + vnoff[c]);
-            dpacc = mfma32(a.v, dof[c].v, dpacc);
-          }
+            a.h[0] = lds_read_tr16(base + ktoff[0][db]);
+            a.h[1] = lds_read_tr16(base + ktoff[1][db]);
+            return a;
+          };
+          LdsChain<2 * NDB, 4> ch2;
+          ch2.prefill(load_kt);  // in flight during the exp / dS arithmetic
           const bool need_mask = kb + 31 > qw0;
           Frag dsf[2];
 #pragma unroll
@@ -182,23 +200,17 @@ __global__ __launch_bounds__(kThreads, (DQK > 128 ? 1 : 2)) void bwd_dq_kernel(c
             float ds[4];
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-              float pr = __builtin_amdgcn_exp2f(sacc[4 * b + v] * p.scale_log2 - lse2);
+              float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[4 * b + v], p.scale_log2, -lse2));
               if (need_mask && kb + 8 * b + 4 * hh + v > q_in) pr = 0.f;
               ds[v] = pr * (dpacc[4 * b + v] - Dv);
             }
             dsf[b >> 1].w[2 * (b & 1)] = pack_bf16(ds[0], ds[1]);
             dsf[b >> 1].w[2 * (b & 1) + 1] = pack_bf16(ds[2], ds[3]);
           }
-#pragma unroll
-          for (int db = 0; db < NDB; ++db)
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-              Frag a;
-              const char* base = kt_lds + (32 * blk + 16 * j) * KRB;
-              a.h[0] = lds_read_tr16(base + ktoff[0][db]);
-              a.h[1] = lds_read_tr16(base + ktoff[1][db]);
-              dqacc[db] = mfma32(a.v, dsf[j].v, dqacc[db]);
-            }
+          __builtin_amdgcn_sched_barrier(0);
+          ch2.run(load_kt, [&](int i, const Frag& a) {
+            dqacc[i % NDB] = mfma32(a.v, dsf[i / NDB].v, dqacc[i % NDB]);
+          });
         }
       }
       if (row_valid) {
@@ -234,7 +246,8 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
   float* const d_lds = lse_lds + 2 * BQ;
 
   const int tid = threadIdx.x;
-  const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
 
   int qoff[NC], dooff[NCV], qtoff[2][NDB], dotoff[2][NEB];
 #pragma unroll
@@ -259,12 +272,18 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
     }
   }
 
+  TileLoader<DQK, BQ> q_loader;
+  TileLoader<DV, BQ> o_loader;
+  q_loader.init(wave, lane);
+  o_loader.init(wave, lane);
+  const uint32_t q_stride_b = (uint32_t)p.q_st * 2, o_stride_b = (uint32_t)p.o_st * 2;
+
   ProfAcc pa;
   for (;;) {
     __syncthreads();
     if (tid == 0) *(volatile int*)smem = atomicAdd(p.counter, 1);
     __syncthreads();
-    const int item = *(volatile int*)smem;
+    const int item = __builtin_amdgcn_readfirstlane(*(volatile int*)smem);
     __syncthreads();
     if (item >= p.n_tiles * p.Hkv) break;
     prof_begin(pa, p.prof, tid);
@@ -297,10 +316,10 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
         const int qb = qb_start + (step % nqb) * BQ;
         const int valid = s_len - qb;  // >= 1
         const int buf = step & 1;
-        async_tile_load<DQK, BQ>(p.q + (int64_t)(s0 + qb) * p.q_st + (int64_t)hq * p.q_sh, p.q_st, valid,
-                                 q_lds + buf * Q_TILE, wave, lane);
-        async_tile_load<DV, BQ>(p.d_o + (int64_t)(s0 + qb) * p.o_st + (int64_t)hq * p.o_sh, p.o_st, valid,
-                                o_lds + buf * O_TILE, wave, lane);
+        q_loader.issue(p.q + (int64_t)(s0 + qb) * p.q_st + (int64_t)hq * p.q_sh, q_stride_b, valid,
+                       q_lds + buf * Q_TILE, wave);
+        o_loader.issue(p.d_o + (int64_t)(s0 + qb) * p.o_st + (int64_t)hq * p.o_sh, o_stride_b, valid,
+                       o_lds + buf * O_TILE, wave);
         if (wave < 2) {
           const int row = lane < valid ? lane : valid - 1;
           const float* src = (wave == 0 ? p.lse : p.D) + (int64_t)hq * p.T + s0 + qb + row;
@@ -349,18 +368,39 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
           f32x16 sacc, dpacc;
 #pragma unroll
           for (int i = 0; i < 16; ++i) sacc[i] = 0.f, dpacc[i] = 0.f;
-#pragma unroll
-          for (int c = 0; c < NC; ++c) {
-            Frag a;
-            a.u = *(const u32x4*)(qt + 32 * sub * QRB + qoff[c]);
-            sacc = mfma32(a.v, knat[c].v, sacc);
+          {
+            // S = Q K^T (steps 0..NC-1) and dP = dO V^T (steps NC..), one read pipeline
+            auto load = [&](int i) {
+              Frag a;
+              if (i < NC) a.u = *(const u32x4*)(qt + 32 * sub * QRB + qoff[i]);
+              else a.u = *(const u32x4*)(ot + 32 * sub * ORB + dooff[i - NC]);
+              return a;
+            };
+            LdsChain<NC + NCV, 6> ch;
+            ch.prefill(load);
+            ch.run(load, [&](int i, const Frag& a) {
+              if (i < NC) sacc = mfma32(a.v, knat[i].v, sacc);
+              else dpacc = mfma32(a.v, vnat[i - NC].v, dpacc);
+            });
           }
-#pragma unroll
-          for (int c = 0; c < NCV; ++c) {
+          // dV^T += dO^T P (steps 0..2*NEB-1), dK^T += Q^T dS (steps 2*NEB..): transposing reads
+          auto load_t = [&](int i) {
             Frag a;
-            a.u = *(const u32x4*)(ot + 32 * sub * ORB + dooff[c]);
-            dpacc = mfma32(a.v, vnat[c].v, dpacc);
-          }
+            if (i < 2 * NEB) {
+              const int eb = i % NEB, j = i / NEB;
+              const char* base = ot + (32 * sub + 16 * j) * ORB;
+              a.h[0] = lds_read_tr16(base + dotoff[0][eb]);
+              a.h[1] = lds_read_tr16(base + dotoff[1][eb]);
+            } else {
+              const int db = (i - 2 * NEB) % NDB, j = (i - 2 * NEB) / NDB;
+              const char* base = qt + (32 * sub + 16 * j) * QRB;
+              a.h[0] = lds_read_tr16(base + qtoff[0][db]);
+              a.h[1] = lds_read_tr16(base + qtoff[1][db]);
+            }
+            return a;
+          };
+          LdsChain<2 * NEB + 2 * NDB, 6> ch2;
+          ch2.prefill(load_t);  // in flight during the exp / dS arithmetic
           // accumulator element 4b+v <-> query q0 + 8b + 4hh + v, key column key_in
           const bool need_mask = kw0_in + 31 > q0 || q0 + 31 >= s_len;
           Frag pb[2], dsb[2];
@@ -371,7 +411,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
             float pv[4], ds[4];
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-              float pr = __builtin_amdgcn_exp2f(sacc[4 * b + v] * p.scale_log2 - l4[v] * kLog2e);
+              float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[4 * b + v], p.scale_log2, -l4[v] * kLog2e));
               if (need_mask) {
                 const int q_in = q0 + 8 * b + 4 * hh + v;
                 if (key_in > q_in || q_in >= s_len) pr = 0.f;
@@ -384,26 +424,11 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
             dsb[b >> 1].w[2 * (b & 1)] = pack_bf16(ds[0], ds[1]);
             dsb[b >> 1].w[2 * (b & 1) + 1] = pack_bf16(ds[2], ds[3]);
           }
-#pragma unroll
-          for (int eb = 0; eb < NEB; ++eb)
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-              Frag a;
-              const char* base = ot + (32 * sub + 16 * j) * ORB;
-              a.h[0] = lds_read_tr16(base + dotoff[0][eb]);
-              a.h[1] = lds_read_tr16(base + dotoff[1][eb]);
-              dvt[eb] = mfma32(a.v, pb[j].v, dvt[eb]);
-            }
-#pragma unroll
-          for (int db = 0; db < NDB; ++db)
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-              Frag a;
-              const char* base = qt + (32 * sub + 16 * j) * QRB;
-              a.h[0] = lds_read_tr16(base + qtoff[0][db]);
-              a.h[1] = lds_read_tr16(base + qtoff[1][db]);
-              dkt[db] = mfma32(a.v, dsb[j].v, dkt[db]);
-            }
+          __builtin_amdgcn_sched_barrier(0);
+          ch2.run(load_t, [&](int i, const Frag& a) {
+            if (i < 2 * NEB) dvt[i % NEB] = mfma32(a.v, pb[i / NEB].v, dvt[i % NEB]);
+            else dkt[(i - 2 * NEB) % NDB] = mfma32(a.v, dsb[(i - 2 * NEB) / NDB].v, dkt[(i - 2 * NEB) % NDB]);
+          });
         }
       }
 

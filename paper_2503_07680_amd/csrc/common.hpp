@@ -41,6 +41,13 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   return __builtin_bit_cast(uint32_t, h);
 }
 
+// acc + lo(w) + hi(w) for a packed bf16 pair (v_dot2c_f32_bf16 with a vector of ones)
+__device__ __forceinline__ float add_bf16_pair(float acc, uint32_t w) {
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), __builtin_bit_cast(bf16x2, 0x3f803f80u),
+                                         acc, false);
+}
+
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
@@ -92,6 +99,57 @@ __device__ __forceinline__ void async_tile_load(const uint16_t* g, int64_t strid
   }
 }
 
+// One 16-byte-per-lane global -> LDS copy: lane i writes LDS bytes [lds_addr + 16 i, +16).  The
+// global address is a wave-uniform 64-bit base plus a 32-bit per-lane byte offset, so no per-lane
+// 64-bit address arithmetic is needed.  Completion is tracked by vmcnt like any vector load.
+__device__ __forceinline__ void async_copy16(const void* base_uniform, uint32_t lane_byte_off,
+                                             uint32_t lds_addr_uniform) {
+  asm volatile(
+      "s_mov_b32 m0, %0\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %1, %2"
+      :
+      : "s"(lds_addr_uniform), "v"(lane_byte_off), "s"(base_uniform)
+      : "memory", "m0");
+}
+
+__device__ __forceinline__ uint32_t lds_address(const void* p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
+}
+
+// Tile copy with the lane-dependent part (LDS row, swizzled chunk) packed once per kernel.  Rows
+// >= rows_valid re-read the last valid row (never out of bounds; the caller masks their products).
+template <int D, int ROWS>
+struct TileLoader {
+  static constexpr int RB = D * 2;
+  static constexpr int N_INSTR = ROWS * RB / 1024;
+  static constexpr int PER_WAVE = (N_INSTR + 3) / 4;
+  uint32_t rc[PER_WAVE];  // (row << 16) | byte offset of the source chunk inside its row
+
+  __device__ __forceinline__ void init(int wave, int lane) {
+#pragma unroll
+    for (int ii = 0; ii < PER_WAVE; ++ii) {
+      const int pos = (wave + 4 * ii) * 1024 + lane * 16;
+      const int row = pos / RB, cpos = (pos % RB) / 16;
+      rc[ii] = ((uint32_t)row << 16) | (uint32_t)(swz<D>(cpos, row) * 16);
+    }
+  }
+  // g: first row of the tile (wave-uniform); stride_bytes < 2^16 * ... fits 32 bits with row < ROWS
+  __device__ __forceinline__ void issue(const uint16_t* g, uint32_t stride_bytes, int rows_valid,
+                                        const char* lds_tile, int wave) const {
+    const uint32_t last = (uint32_t)(rows_valid - 1);
+    const uint32_t lds0 = lds_address(lds_tile);
+#pragma unroll
+    for (int ii = 0; ii < PER_WAVE; ++ii) {
+      const int inst = wave + 4 * ii;
+      if (N_INSTR % 4 != 0 && inst >= N_INSTR) break;
+      const uint32_t row = rc[ii] >> 16;
+      const uint32_t off = __umul24(row < last ? row : last, stride_bytes) + (rc[ii] & 0xffffu);
+      async_copy16(g, off, lds0 + inst * 1024);
+    }
+  }
+};
+
 // all of this wave's outstanding global loads (including global -> LDS copies) have completed
 __device__ __forceinline__ void wait_async_loads() {
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0), expcnt and lgkmcnt left at their maxima
@@ -102,6 +160,29 @@ __device__ __forceinline__ void wait_async_loads() {
 __device__ __forceinline__ s16x4 lds_read_tr16(const char* addr) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)addr);
 }
+
+// A chain of L MFMAs whose A operands come from LDS, with the reads running PD fragments ahead of
+// their use.  load(i) returns fragment i, mma(i, frag) consumes it.  prefill()/run() are split so a
+// caller can start the first reads before unrelated arithmetic and drain the chain after it.
+template <int L, int PD>
+struct LdsChain {
+  Frag ring[PD];
+  template <class Load>
+  __device__ __forceinline__ void prefill(Load load) {
+#pragma unroll
+    for (int i = 0; i < PD && i < L; ++i) ring[i] = load(i);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  template <class Load, class Mma>
+  __device__ __forceinline__ void run(Load load, Mma mma) {
+#pragma unroll
+    for (int i = 0; i < L; ++i) {
+      mma(i, ring[i % PD]);
+      if (i + PD < L) ring[i % PD] = load(i + PD);
+      __builtin_amdgcn_sched_barrier(0);  // keep the read-ahead distance: no hoisting or sinking
+    }
+  }
+};
 
 // Position of contraction index w (0..15) inside a 16-element chunk of a transposed LDS tile.
 // An MFMA whose B operand is taken straight from an accumulator sees, in lane half hh, the

@@ -17,6 +17,99 @@
 
 namespace hbp {
 
+// One key tile (64 keys) for one wavefront (32 query rows).  MASKED: the tile reaches past the
+// wave's first query row, so the causal compare is applied; interior tiles skip it entirely.
+// LDS operand reads run PD fragments ahead of the MFMAs that consume them.
+template <int DQK, int DV, bool MASKED>
+__device__ __forceinline__ void fwd_tile(const char* kt_lds, const char* vt_lds, const int (&koff)[DQK / 16],
+                                         const int (&voff)[2][DV / 32], const Frag (&qf)[DQK / 16],
+                                         f32x16 (&oacc)[DV / 32], float& m_run, float& l_run,
+                                         float scale_log2, int k_off, int q_in, int hh) {
+  constexpr int KRB = DQK * 2, VRB = DV * 2;
+  constexpr int NC = DQK / 16, NEB = DV / 32;
+  constexpr int PD = 4;
+
+  f32x16 sacc[2];
+#pragma unroll
+  for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) sacc[blk][i] = 0.f;
+  {
+    constexpr int L = 2 * NC;
+    Frag ring[PD];
+#pragma unroll
+    for (int i = 0; i < PD; ++i) ring[i].u = *(const u32x4*)(kt_lds + 32 * (i / NC) * KRB + koff[i % NC]);
+#pragma unroll
+    for (int i = 0; i < L; ++i) {
+      sacc[i / NC] = mfma32(ring[i % PD].v, qf[i % NC].v, sacc[i / NC]);
+      if (i + PD < L)
+        ring[i % PD].u = *(const u32x4*)(kt_lds + 32 * ((i + PD) / NC) * KRB + koff[(i + PD) % NC]);
+      __builtin_amdgcn_sched_barrier(0);  // keep the read-ahead distance: no hoisting of later reads
+    }
+  }
+  // first V fragments: their LDS latency hides under the softmax arithmetic
+  constexpr int LV = 4 * NEB;  // steps (blk, j, eb), eb fastest
+  Frag vring[PD];
+  auto load_v = [&](int i) {
+    const int eb = i % NEB, bj = i / NEB;  // bj = 2*blk + j
+    const char* base = vt_lds + 16 * bj * VRB;
+    Frag f;
+    f.h[0] = lds_read_tr16(base + voff[0][eb]);
+    f.h[1] = lds_read_tr16(base + voff[1][eb]);
+    return f;
+  };
+#pragma unroll
+  for (int i = 0; i < PD; ++i) vring[i] = load_v(i);
+  __builtin_amdgcn_sched_barrier(0);
+
+  float mx = -INFINITY;
+#pragma unroll
+  for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      if (MASKED) {
+        const int key_in = k_off + 32 * blk + 8 * (i >> 2) + 4 * hh + (i & 3);
+        if (key_in > q_in) sacc[blk][i] = -INFINITY;
+      }
+      mx = fmaxf(mx, sacc[blk][i]);
+    }
+  mx = max_with_other_half(mx) * scale_log2;  // scale > 0: max commutes with the scaling
+  // Lazy rescale: the running reference m_run only moves when some row's maximum grew by more
+  // than 2^8; until then probabilities are taken relative to the old reference (they stay below
+  // 2^8, exact in fp32/bf16 range, and O and l use the same reference so the result is unchanged).
+  if (__builtin_amdgcn_ballot_w64(mx > m_run + 8.0f) != 0) {
+    const float m_new = fmaxf(m_run, mx);  // finite: key 0 of the sample is visible to every row
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    m_run = m_new;
+    l_run *= alpha;
+#pragma unroll
+    for (int eb = 0; eb < NEB; ++eb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) oacc[eb][i] *= alpha;
+  }
+  Frag pf[4];  // index 2*blk + j
+  float psum = 0.f;
+#pragma unroll
+  for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[blk][8 * j + 2 * w], scale_log2, -m_run));
+        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[blk][8 * j + 2 * w + 1], scale_log2, -m_run));
+        pf[2 * blk + j].w[w] = pack_bf16(p0, p1);
+        psum += p0 + p1;  // unrounded: LSE must not inherit the bf16 rounding of P
+      }
+  l_run += psum;
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int i = 0; i < LV; ++i) {
+    oacc[i % NEB] = mfma32(vring[i % PD].v, pf[i / NEB].v, oacc[i % NEB]);
+    if (i + PD < LV) vring[i % PD] = load_v(i + PD);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
 template <int DQK, int DV>
 __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(const FwdParams p) {
   constexpr int BM = 128, BN = 64;
@@ -31,7 +124,8 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(const FwdParams p) {
   char* const v_lds = smem + 2 * K_TILE;
 
   const int tid = threadIdx.x;
-  const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
 
   // per-lane LDS byte offsets of the A operands (row part that does not depend on the 32-key block)
   int koff[NC];
@@ -49,6 +143,11 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(const FwdParams p) {
         voff[r][eb] = (8 * r + k8) * VRB + swz<DV>(c, 8 * r + k8) * 16 + (s & 1) * 8;
       }
   }
+  TileLoader<DQK, BN> k_loader;
+  TileLoader<DV, BN> v_loader;
+  k_loader.init(wave, lane);
+  v_loader.init(wave, lane);
+  const uint32_t k_stride_b = (uint32_t)p.k_st * 2, v_stride_b = (uint32_t)p.v_st * 2;
 
   uint32_t n_done = 0;
   uint64_t t_first = 0, t_last = 0, t_busy = 0;
@@ -57,7 +156,7 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(const FwdParams p) {
     __syncthreads();  // all LDS reads of the previous item are finished
     if (tid == 0) *(volatile int*)smem = atomicAdd(p.counter, 1);
     __syncthreads();
-    const int item = *(volatile int*)smem;
+    const int item = __builtin_amdgcn_readfirstlane(*(volatile int*)smem);
     __syncthreads();
     if (item >= p.n_tiles * p.Hq) break;
     uint64_t t0 = 0;
@@ -92,10 +191,8 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(const FwdParams p) {
       auto issue = [&](int kt) {
         const int k_off = kt * BN;
         const int valid = n_keys - k_off;  // >= 1
-        async_tile_load<DQK, BN>(kbase + (int64_t)k_off * p.k_st, p.k_st, valid,
-                                 k_lds + (kt & 1) * K_TILE, wave, lane);
-        async_tile_load<DV, BN>(vbase + (int64_t)k_off * p.v_st, p.v_st, valid,
-                                v_lds + (kt & 1) * V_TILE, wave, lane);
+        k_loader.issue(kbase + (int64_t)k_off * p.k_st, k_stride_b, valid, k_lds + (kt & 1) * K_TILE, wave);
+        v_loader.issue(vbase + (int64_t)k_off * p.v_st, v_stride_b, valid, v_lds + (kt & 1) * V_TILE, wave);
       };
       issue(0);
 
@@ -116,6 +213,7 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(const FwdParams p) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) oacc[eb][i] = 0.f;
       float m_run = -INFINITY, l_run = 0.f;
+      const int q_in = qw0 + l32;
 
       for (int kt = 0; kt < nkt; ++kt) {
         wait_async_loads();
@@ -126,69 +224,10 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(const FwdParams p) {
         if (!wave_active || k_off > qw0 + 31) continue;  // nothing at or below the diagonal
         const char* kt_lds = k_lds + (kt & 1) * K_TILE;
         const char* vt_lds = v_lds + (kt & 1) * V_TILE;
-
-        f32x16 sacc[2];
-#pragma unroll
-        for (int blk = 0; blk < 2; ++blk) {
-#pragma unroll
-          for (int i = 0; i < 16; ++i) sacc[blk][i] = 0.f;
-#pragma unroll
-          for (int c = 0; c < NC; ++c) {
-            Frag kf;
-            kf.u = *(const u32x4*)(kt_lds + 32 * blk * KRB + koff[c]);
-            sacc[blk] = mfma32(kf.v, qf[c].v, sacc[blk]);
-          }
-        }
-        // scale into the base-2 domain, causal mask on tiles that reach past the wave's first row
-        const bool need_mask = k_off + BN - 1 > qw0;
-        const int q_in = qw0 + l32;
-        float mx = -INFINITY;
-#pragma unroll
-        for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            float x = sacc[blk][i] * p.scale_log2;
-            if (need_mask) {
-              const int key_in = k_off + 32 * blk + 8 * (i >> 2) + 4 * hh + (i & 3);
-              if (key_in > q_in) x = -INFINITY;
-            }
-            sacc[blk][i] = x;
-            mx = fmaxf(mx, x);
-          }
-        mx = max_with_other_half(mx);
-        const float m_new = fmaxf(m_run, mx);  // finite: key 0 of the sample is visible to every row
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-        m_run = m_new;
-        float psum = 0.f;
-        Frag pf[2][2];
-#pragma unroll
-        for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-          for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int w = 0; w < 4; ++w) {
-              const float p0 = __builtin_amdgcn_exp2f(sacc[blk][8 * j + 2 * w] - m_new);
-              const float p1 = __builtin_amdgcn_exp2f(sacc[blk][8 * j + 2 * w + 1] - m_new);
-              psum += p0 + p1;
-              pf[blk][j].w[w] = pack_bf16(p0, p1);
-            }
-        l_run = l_run * alpha + psum;
-#pragma unroll
-        for (int eb = 0; eb < NEB; ++eb)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) oacc[eb][i] *= alpha;
-#pragma unroll
-        for (int eb = 0; eb < NEB; ++eb)
-#pragma unroll
-          for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-              Frag vf;
-              const char* base = vt_lds + (32 * blk + 16 * j) * VRB;
-              vf.h[0] = lds_read_tr16(base + voff[0][eb]);
-              vf.h[1] = lds_read_tr16(base + voff[1][eb]);
-              oacc[eb] = mfma32(vf.v, pf[blk][j].v, oacc[eb]);
-            }
+        if (k_off + BN - 1 > qw0)
+          fwd_tile<DQK, DV, true>(kt_lds, vt_lds, koff, voff, qf, oacc, m_run, l_run, p.scale_log2, k_off, q_in, hh);
+        else
+          fwd_tile<DQK, DV, false>(kt_lds, vt_lds, koff, voff, qf, oacc, m_run, l_run, p.scale_log2, k_off, q_in, hh);
       }
 
       // finalise: O = acc / l, LSE = (m + log2 l) * ln 2
