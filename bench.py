@@ -119,6 +119,9 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="workload 1..5 (default 3: the mixed 32K pack)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one 256 MiB device-to-device copy (known size) to scale rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); --gpus %d is not "
@@ -185,6 +188,13 @@ def main():
     spread_f = busy_spread(pa.profile_records(H.HBP_FWD))
     spread_b = busy_spread(pa.profile_records(H.HBP_BWD))
     spread_q = busy_spread(pa.profile_records(H.HBP_BWD_DQ))
+
+    if args.calib_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
 
     value = (fwd_flops + bwd_flops) / (ms_per_step * 1e-3) / 1e12
     # flops of the launches themselves: the dK/dV kernel does 4 of the backward's products

@@ -7,7 +7,7 @@
 namespace {
 
 constexpr int kNumCU = 256;          // MI355X: 8 accelerator dies x 32 compute units
-constexpr size_t kCounterBytes = 256;
+constexpr size_t kCounterBytes = 2048;  // two sets of 8 per-die counters, 128 bytes apart
 
 bool dims_supported(int d_qk, int d_v) {
   return (d_qk == 64 && d_v == 64) || (d_qk == 128 && d_v == 128) || (d_qk == 192 && d_v == 128);
@@ -57,7 +57,7 @@ struct BwdLayout {
 
 BwdLayout bwd_layout(const hbp_attn_desc* d) {
   BwdLayout l;
-  l.d_off = kCounterBytes;  // two counters, 128 bytes apart, in the first 256 bytes
+  l.d_off = kCounterBytes;
   l.total = align_up(l.d_off + (size_t)d->n_q_heads * d->total_tokens * sizeof(float), 256);
   return l;
 }
@@ -161,7 +161,7 @@ extern "C" hbp_status hbp_varlen_attn_fwd(const hbp_attn_desc* desc, const void*
   p.prof = profile;
 
   hipStream_t hs = static_cast<hipStream_t>(stream);
-  if (hbp::launch_zero_counter(p.counter, hs) != 0) return HBP_ERR_DEVICE;
+  if (hbp::launch_zero_counters(p.counter, hs) != 0) return HBP_ERR_DEVICE;
   const int grid = grid_for((int64_t)n_q_tiles * p.Hq, 2);
   if (hbp::launch_fwd(desc->d_qk, desc->d_v, p, grid, hs, g_events[HBP_FWD][0], g_events[HBP_FWD][1]) != 0) return HBP_ERR_DEVICE;
   return HBP_OK;
@@ -202,7 +202,7 @@ extern "C" hbp_status hbp_varlen_attn_bwd(const hbp_attn_desc* desc, const void*
   p.dv = static_cast<uint16_t*>(dv);
   char* ws = static_cast<char*>(workspace);
   p.counter = reinterpret_cast<int32_t*>(ws);
-  p.counter_dq = reinterpret_cast<int32_t*>(ws + 128);
+  p.counter_dq = reinterpret_cast<int32_t*>(ws + 1024);
   p.D = reinterpret_cast<float*>(ws + lay.d_off);
   p.cu = cu_seqlens;
   p.tiles = kv_tiles;

@@ -1,6 +1,6 @@
 // Backward kernels: dQ, dK, dV of causal attention inside each sample of a packed buffer, gfx950.
 //
-// (1) prepass   D[h,r] = sum_x dO[r,h,x] O[r,h,x]; resets the two scheduler counters.
+// (1) prepass   D[h,r] = sum_x dO[r,h,x] O[r,h,x]; resets the scheduler counters of (2) and (3).
 // (2) dq        query-tile major, same skeleton as the forward: work item = (query tile of <=128
 //               rows, query head); K and V tiles of 64 keys stream through LDS; per 32-key block
 //                   S^T  = K Q^T,  dP^T = V dO^T          (one query per lane column)
@@ -93,17 +93,14 @@ __global__ __launch_bounds__(kThreads, (DQK > 128 ? 1 : 2)) void bwd_dq_kernel(c
   const uint32_t k_stride_b = (uint32_t)p.k_st * 2, v_stride_b = (uint32_t)p.v_st * 2;
 
   ProfAcc pa;
+  const WorkQueues wq{p.counter_dq, p.n_q_tiles, p.Hkv, p.g};
+  int q_cur = xcc_id_reg() & (kNumXcd - 1), q_tried = 0;
   for (;;) {
-    __syncthreads();
-    if (tid == 0) *(volatile int*)smem = atomicAdd(p.counter_dq, 1);
-    __syncthreads();
-    const int item = __builtin_amdgcn_readfirstlane(*(volatile int*)smem);
-    __syncthreads();
-    if (item >= p.n_q_tiles * p.Hq) break;
+    int tile_idx, h;
+    if (!next_item(wq, (int*)smem, tid, q_cur, q_tried, tile_idx, h)) break;
     prof_begin(pa, p.prof_dq, tid);
 
-    const int h = item % p.Hq;
-    const hbp_tile tl = p.q_tiles[item / p.Hq];
+    const hbp_tile tl = p.q_tiles[tile_idx];
     bool ok = tl.sample >= 0 && tl.sample < p.n_samples;
     int s0 = 0, s1 = 0;
     if (ok) {
@@ -279,17 +276,14 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
   const uint32_t q_stride_b = (uint32_t)p.q_st * 2, o_stride_b = (uint32_t)p.o_st * 2;
 
   ProfAcc pa;
+  const WorkQueues wq{p.counter, p.n_tiles, p.Hkv, 1};
+  int q_cur = xcc_id_reg() & (kNumXcd - 1), q_tried = 0;
   for (;;) {
-    __syncthreads();
-    if (tid == 0) *(volatile int*)smem = atomicAdd(p.counter, 1);
-    __syncthreads();
-    const int item = __builtin_amdgcn_readfirstlane(*(volatile int*)smem);
-    __syncthreads();
-    if (item >= p.n_tiles * p.Hkv) break;
+    int tile_idx, kh;
+    if (!next_item(wq, (int*)smem, tid, q_cur, q_tried, tile_idx, kh)) break;
     prof_begin(pa, p.prof, tid);
 
-    const int kh = item % p.Hkv;
-    const hbp_tile tl = p.tiles[item / p.Hkv];
+    const hbp_tile tl = p.tiles[tile_idx];
     bool ok = tl.sample >= 0 && tl.sample < p.n_samples;
     int s0 = 0, s1 = 0;
     if (ok) {
@@ -462,9 +456,9 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
 template <int DV>
 __global__ __launch_bounds__(kThreads) void bwd_prepass_kernel(const BwdParams p) {
   constexpr int LPR = DV / 8;  // lanes per (row, head): 16 bytes of O and dO each
-  if (blockIdx.x == 0 && threadIdx.x == 0) {
-    *p.counter = 0;
-    *p.counter_dq = 0;
+  if (blockIdx.x == 0 && threadIdx.x < kNumXcd) {
+    p.counter[threadIdx.x * kCounterStride] = 0;
+    p.counter_dq[threadIdx.x * kCounterStride] = 0;
   }
   const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   const int64_t rh = gid / LPR;

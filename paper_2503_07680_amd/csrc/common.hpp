@@ -199,6 +199,64 @@ __device__ __forceinline__ uint32_t xcc_id_reg() {
   return __builtin_amdgcn_s_getreg((31 << 11) | (0 << 6) | 20);
 }
 
+// ---- work queues, one per accelerator die (XCD) ------------------------------------------------
+// Each die has its own L2, so work is dealt by kv head: queue x holds, in worklist order, the items
+// of the kv heads kvh with kvh % 8 == x.  All workgroups of a die then stream the same K/V (or the
+// same Q/dO) and share it through that die's L2.  A workgroup serves its own die's queue first and
+// then steals from the others, so every item is done whatever the head count and the tail stays
+// balanced.  Counters are 128 bytes apart.
+constexpr int kNumXcd = 8;
+constexpr int kCounterStride = 32;  // in int32
+
+struct WorkQueues {
+  int32_t* counters;
+  int n_tiles, Hkv, per_kv;  // per_kv: heads per kv head inside one item group (g, or 1)
+
+  __device__ __forceinline__ int length(int x) const {
+    const int nk = Hkv > x ? (Hkv - x + kNumXcd - 1) / kNumXcd : 0;
+    return n_tiles * nk * per_kv;
+  }
+  // Called by one thread.  q_cur / q_tried: that thread's cursor over the queues.  Returns false
+  // when every queue is exhausted; else the tile index and the head (kvh * per_kv + sub).
+  __device__ __forceinline__ bool take(int& q_cur, int& q_tried, int& tile_idx, int& head) const {
+    while (q_tried < kNumXcd) {
+      const int len = length(q_cur);
+      if (len > 0) {
+        const int j = atomicAdd(counters + q_cur * kCounterStride, 1);
+        if (j < len) {
+          const int nk = (Hkv - q_cur + kNumXcd - 1) / kNumXcd;
+          const int per_tile = nk * per_kv;
+          const int rem = j % per_tile;
+          tile_idx = j / per_tile;
+          head = (q_cur + kNumXcd * (rem / per_kv)) * per_kv + rem % per_kv;
+          return true;
+        }
+      }
+      q_cur = (q_cur + 1) & (kNumXcd - 1);
+      ++q_tried;
+    }
+    return false;
+  }
+};
+
+// Workgroup-wide fetch of the next item: thread 0 takes it, everybody reads it back as scalars.
+// slot: two ints of LDS that nobody else touches between the surrounding barriers.
+__device__ __forceinline__ bool next_item(const WorkQueues& wq, int* slot, int tid, int& q_cur, int& q_tried,
+                                          int& tile_idx, int& head) {
+  __syncthreads();  // all LDS reads of the previous item are finished
+  if (tid == 0) {
+    int t = -1, h = 0;
+    if (!wq.take(q_cur, q_tried, t, h)) t = -1;
+    ((volatile int*)slot)[0] = t;
+    ((volatile int*)slot)[1] = h;
+  }
+  __syncthreads();
+  tile_idx = __builtin_amdgcn_readfirstlane(((volatile int*)slot)[0]);
+  head = __builtin_amdgcn_readfirstlane(((volatile int*)slot)[1]);
+  __syncthreads();
+  return tile_idx >= 0;
+}
+
 struct FwdParams {
   const uint16_t *q, *k, *v;
   uint16_t* o;
@@ -232,6 +290,6 @@ struct BwdParams {
 int launch_fwd(int d_qk, int d_v, const FwdParams& p, int grid, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
 // ev: {dkdv start, dkdv stop, dq start, dq stop}, entries may be null
 int launch_bwd(int d_qk, int d_v, const BwdParams& p, int grid_dq, int grid_dkdv, hipStream_t s, hipEvent_t* ev);
-int launch_zero_counter(int32_t* counter, hipStream_t s);
+int launch_zero_counters(int32_t* counters, hipStream_t s);  // the kNumXcd forward counters
 
 }  // namespace hbp

@@ -152,21 +152,18 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(const FwdParams p) {
   uint32_t n_done = 0;
   uint64_t t_first = 0, t_last = 0, t_busy = 0;
 
+  const WorkQueues wq{p.counter, p.n_tiles, p.Hkv, p.g};
+  int q_cur = xcc_id_reg() & (kNumXcd - 1), q_tried = 0;
   for (;;) {
-    __syncthreads();  // all LDS reads of the previous item are finished
-    if (tid == 0) *(volatile int*)smem = atomicAdd(p.counter, 1);
-    __syncthreads();
-    const int item = __builtin_amdgcn_readfirstlane(*(volatile int*)smem);
-    __syncthreads();
-    if (item >= p.n_tiles * p.Hq) break;
+    int tile_idx, h;
+    if (!next_item(wq, (int*)smem, tid, q_cur, q_tried, tile_idx, h)) break;
     uint64_t t0 = 0;
     if (p.prof && tid == 0) {
       t0 = wall_clock64();
       if (n_done == 0) t_first = t0;
     }
 
-    const int h = item % p.Hq;
-    const hbp_tile tl = p.tiles[item / p.Hq];
+    const hbp_tile tl = p.tiles[tile_idx];
     bool ok = tl.sample >= 0 && tl.sample < p.n_samples;
     int s0 = 0, s1 = 0;
     if (ok) {
@@ -267,12 +264,12 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(const FwdParams p) {
   }
 }
 
-__global__ void zero_counter_kernel(int32_t* c) {
-  if (threadIdx.x == 0) *c = 0;
+__global__ void zero_counters_kernel(int32_t* c) {
+  if (threadIdx.x < kNumXcd) c[threadIdx.x * kCounterStride] = 0;
 }
 
-int launch_zero_counter(int32_t* counter, hipStream_t s) {
-  hipLaunchKernelGGL(zero_counter_kernel, dim3(1), dim3(64), 0, s, counter);
+int launch_zero_counters(int32_t* counters, hipStream_t s) {
+  hipLaunchKernelGGL(zero_counters_kernel, dim3(1), dim3(64), 0, s, counters);
   return (int)hipGetLastError();
 }
 

@@ -69,18 +69,19 @@ def test_launch_entry_points_reject_bad_arguments_before_touching_the_device():
     lib = H.load_library()
     d = desc()
     fake = 0x1000  # never dereferenced: every call below fails validation first
+    wsf = H.hbp_workspace_bytes(d, H.HBP_FWD)
     # null descriptor
-    assert lib.hbp_varlen_attn_fwd(None, fake, fake, fake, fake, fake, 1, fake, fake, fake, 256, None, None) == 1
+    assert lib.hbp_varlen_attn_fwd(None, fake, fake, fake, fake, fake, 1, fake, fake, fake, wsf, None, None) == 1
     # missing / misaligned / small workspace
     assert lib.hbp_varlen_attn_fwd(ctypes.byref(d), fake, fake, fake, fake, fake, 1, fake, fake, None, 0, None, None) == 5
-    assert lib.hbp_varlen_attn_fwd(ctypes.byref(d), fake, fake, fake, fake, fake, 1, fake, fake, 0x1010, 256, None, None) == 5
+    assert lib.hbp_varlen_attn_fwd(ctypes.byref(d), fake, fake, fake, fake, fake, 1, fake, fake, 0x1010, wsf, None, None) == 5
     assert lib.hbp_varlen_attn_fwd(ctypes.byref(d), fake, fake, fake, fake, fake, 1, fake, fake, fake, 8, None, None) == 5
     assert lib.hbp_varlen_attn_bwd(ctypes.byref(d), fake, fake, fake, fake, fake, fake, fake, fake, 1, fake, 1,
                                    fake, fake, fake, fake, 1024, None, None, None) == 5
     # null tensors, negative tile count, misaligned tensor
-    assert lib.hbp_varlen_attn_fwd(ctypes.byref(d), None, fake, fake, fake, fake, 1, fake, fake, fake, 256, None, None) == 1
-    assert lib.hbp_varlen_attn_fwd(ctypes.byref(d), fake, fake, fake, fake, fake, -1, fake, fake, fake, 256, None, None) == 1
-    assert lib.hbp_varlen_attn_fwd(ctypes.byref(d), 0x1008, fake, fake, fake, fake, 1, fake, fake, fake, 256, None, None) == 1
+    assert lib.hbp_varlen_attn_fwd(ctypes.byref(d), None, fake, fake, fake, fake, 1, fake, fake, fake, wsf, None, None) == 1
+    assert lib.hbp_varlen_attn_fwd(ctypes.byref(d), fake, fake, fake, fake, fake, -1, fake, fake, fake, wsf, None, None) == 1
+    assert lib.hbp_varlen_attn_fwd(ctypes.byref(d), 0x1008, fake, fake, fake, fake, 1, fake, fake, fake, wsf, None, None) == 1
     big = H.hbp_workspace_bytes(d, H.HBP_BWD)
     assert lib.hbp_varlen_attn_bwd(ctypes.byref(d), fake, fake, fake, fake, fake, None, fake, fake, 1, fake, 1,
                                    fake, fake, fake, fake, big, None, None, None) == 1
@@ -88,8 +89,8 @@ def test_launch_entry_points_reject_bad_arguments_before_touching_the_device():
                                    fake, fake, fake, fake, big, None, None, None) == 1
     # empty problems are no-ops that launch nothing
     d0 = desc(total_tokens=0, n_samples=0)
-    assert lib.hbp_varlen_attn_fwd(ctypes.byref(d0), None, None, None, None, None, 0, None, None, fake, 256, None, None) == 0
-    assert lib.hbp_varlen_attn_fwd(ctypes.byref(d), fake, fake, fake, fake, fake, 0, fake, fake, fake, 256, None, None) == 0
+    assert lib.hbp_varlen_attn_fwd(ctypes.byref(d0), None, None, None, None, None, 0, None, None, fake, wsf, None, None) == 0
+    assert lib.hbp_varlen_attn_fwd(ctypes.byref(d), fake, fake, fake, fake, fake, 0, fake, fake, fake, wsf, None, None) == 0
 
 
 def test_product_package_never_imports_the_oracle():
