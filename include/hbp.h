@@ -98,7 +98,7 @@ hbp_status hbp_tile_rows(int32_t d_qk, int32_t d_v, int32_t which, int32_t* rows
 
 /* Bytes of device workspace a call needs (256-byte aligned base required).
  * which = HBP_FWD or HBP_BWD.  Forward: the scheduler's per-die queue counters.  Backward: two
- * sets of counters and the per-row D = rowsum(dO*O) [Hq,T] fp32. */
+ * sets of counters, the per-row D = rowsum(dO*O) and LSE*log2(e), both [Hq,T] fp32. */
 hbp_status hbp_workspace_bytes(const hbp_attn_desc* desc, int32_t which, size_t* bytes_out);
 
 /* Optional per-workgroup record written by the persistent kernels when `profile` != NULL

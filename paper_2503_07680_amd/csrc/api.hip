@@ -52,13 +52,15 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct BwdLayout {
-  size_t d_off, total;
+  size_t d_off, lse2_off, total;
 };
 
 BwdLayout bwd_layout(const hbp_attn_desc* d) {
   BwdLayout l;
   l.d_off = kCounterBytes;
-  l.total = align_up(l.d_off + (size_t)d->n_q_heads * d->total_tokens * sizeof(float), 256);
+  const size_t rows = align_up((size_t)d->n_q_heads * d->total_tokens * sizeof(float), 256);
+  l.lse2_off = l.d_off + rows;
+  l.total = l.lse2_off + rows;
   return l;
 }
 
@@ -204,6 +206,7 @@ extern "C" hbp_status hbp_varlen_attn_bwd(const hbp_attn_desc* desc, const void*
   p.counter = reinterpret_cast<int32_t*>(ws);
   p.counter_dq = reinterpret_cast<int32_t*>(ws + 1024);
   p.D = reinterpret_cast<float*>(ws + lay.d_off);
+  p.lse2 = reinterpret_cast<float*>(ws + lay.lse2_off);
   p.cu = cu_seqlens;
   p.tiles = kv_tiles;
   p.n_tiles = n_kv_tiles;

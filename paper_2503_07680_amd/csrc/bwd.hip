@@ -15,6 +15,8 @@
 //                   dV^T += dO^T P,  dK^T += Q^T dS        (transposing LDS reads of dO and Q)
 // No atomics: dQ has its own pass (S and dP are recomputed there), so every output is written
 // once and the results are bit-stable from run to run.
+#include <type_traits>
+
 #include "common.hpp"
 
 namespace hbp {
@@ -139,7 +141,7 @@ __global__ __launch_bounds__(kThreads, (DQK > 128 ? 1 : 2)) void bwd_dq_kernel(c
 #pragma unroll
         for (int c = 0; c < NCV; ++c) dof[c].u = row_valid ? *(const u32x4*)(dop + 16 * c) : u32x4{0, 0, 0, 0};
         if (row_valid) {
-          lse2 = p.lse[(int64_t)h * p.T + my_row] * kLog2e;
+          lse2 = p.lse2[(int64_t)h * p.T + my_row];
           Dv = p.D[(int64_t)h * p.T + my_row];
         }
       }
@@ -250,7 +252,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
 #pragma unroll
   for (int c = 0; c < NC; ++c) qoff[c] = l32 * QRB + swz<DQK>(2 * c + hh, l32) * 16;
 #pragma unroll
-  for (int c = 0; c < NCV; ++c) dooff[c] = l32 * ORB + swz<DV>(2 * c + hh, l32) * 16;
+  for (int c = 0; c < NCV; ++c) dooff[c] = 2 * Q_TILE + l32 * ORB + swz<DV>(2 * c + hh, l32) * 16;
   {
     const int G = lane >> 4, s = lane & 15;
     const int k8 = 4 * hh + (s >> 2);
@@ -264,10 +266,13 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
 #pragma unroll
       for (int eb = 0; eb < NEB; ++eb) {
         const int c = 4 * eb + 2 * (G & 1) + ((s & 3) >> 1);
-        dotoff[r][eb] = (8 * r + k8) * ORB + swz<DV>(c, 8 * r + k8) * 16 + (s & 1) * 8;
+        dotoff[r][eb] = 2 * Q_TILE + (8 * r + k8) * ORB + swz<DV>(c, 8 * r + k8) * 16 + (s & 1) * 8;
       }
     }
   }
+  // byte offsets (from smem) of this lane's LSE2 / D rows inside the current buffer
+  int lseoff = 2 * Q_TILE + 2 * O_TILE + 16 * hh;
+  int dvoff = lseoff + 2 * BQ * 4;
 
   TileLoader<DQK, BQ> q_loader;
   TileLoader<DV, BQ> o_loader;
@@ -315,11 +320,12 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
         o_loader.issue(p.d_o + (int64_t)(s0 + qb) * p.o_st + (int64_t)hq * p.o_sh, o_stride_b, valid,
                        o_lds + buf * O_TILE, wave);
         if (wave < 2) {
+          // issued through the same untracked path as the tiles: the compiler must not see an LDS
+          // write here, or it would drain every outstanding copy before the next LDS read
           const int row = lane < valid ? lane : valid - 1;
-          const float* src = (wave == 0 ? p.lse : p.D) + (int64_t)hq * p.T + s0 + qb + row;
-          float* dst = (wave == 0 ? lse_lds : d_lds) + buf * BQ;
-          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                           (__attribute__((address_space(3))) void*)dst, 4, 0, 0);
+          const float* src = (wave == 0 ? p.lse2 : p.D) + (int64_t)hq * p.T + s0 + qb;
+          const float* dst = (wave == 0 ? lse_lds : d_lds) + buf * BQ;
+          async_copy4(src, (uint32_t)row * 4u, lds_address(dst));
         }
       };
       if (n_steps > 0) issue(0);
@@ -333,6 +339,12 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
         for (int c = 0; c < NC; ++c) knat[c].u = key_valid ? *(const u32x4*)(kp + 16 * c) : u32x4{0, 0, 0, 0};
 #pragma unroll
         for (int c = 0; c < NCV; ++c) vnat[c].u = key_valid ? *(const u32x4*)(vp + 16 * c) : u32x4{0, 0, 0, 0};
+        // these fragments are only ever MFMA operands: park them in the accumulator register file
+        // so the vector file keeps room for the arithmetic (no copies: MFMA reads either file)
+#pragma unroll
+        for (int c = 0; c < NC; ++c) asm volatile("" : "+a"(knat[c].u));
+#pragma unroll
+        for (int c = 0; c < NCV; ++c) asm volatile("" : "+a"(vnat[c].u));
       }
       f32x16 dkt[NDB], dvt[NEB];
 #pragma unroll
@@ -344,86 +356,162 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
 #pragma unroll
         for (int i = 0; i < 16; ++i) dvt[eb][i] = 0.f;
 
-      for (int step = 0; step < n_steps; ++step) {
-        wait_async_loads();
-        __syncthreads();
-        if (step + 1 < n_steps) issue(step + 1);
+      // One 32-query x 32-key sub-block: sd = (S, dP) products, sm = probabilities and dS,
+      // gr = dV^T / dK^T updates.  Away from the diagonal two sub-blocks are software-pipelined
+      // inside the wave so the vector arithmetic of one is spread, one element per MFMA, behind the
+      // other's MFMAs (the matrix pipe leaves about half of each MFMA's issue time free):
+      //     sd(A) | sd(B) + sm(A) | gr(A) + sm(B) | gr(B)
+      // Blocks that touch the diagonal or the sample tail take the plain masked path.
+      // All LDS offsets already contain the current buffer's base (toggled once per step).
+      struct Sub {
+        f32x16 s, dp;
+        Frag pb[2], dsb[2];
+      };
+      auto do_step = [&](int step) {
         const int qb = qb_start + (step % nqb) * BQ;
-        if (!wave_active || qb + BQ - 1 < kw0_in) continue;  // block lies above this wave's keys
-        const int buf = step & 1;
-        const char* qt = q_lds + buf * Q_TILE;
-        const char* ot = o_lds + buf * O_TILE;
-        const float* lse_b = lse_lds + buf * BQ;
-        const float* d_b = d_lds + buf * BQ;
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub) {
-          const int q0 = qb + 32 * sub;  // in-sample index of the sub-block's first query
-          if (q0 + 31 < kw0_in || q0 >= s_len) continue;
-          f32x16 sacc, dpacc;
-#pragma unroll
-          for (int i = 0; i < 16; ++i) sacc[i] = 0.f, dpacc[i] = 0.f;
-          {
-            // S = Q K^T (steps 0..NC-1) and dP = dO V^T (steps NC..), one read pipeline
-            auto load = [&](int i) {
-              Frag a;
-              if (i < NC) a.u = *(const u32x4*)(qt + 32 * sub * QRB + qoff[i]);
-              else a.u = *(const u32x4*)(ot + 32 * sub * ORB + dooff[i - NC]);
-              return a;
-            };
-            LdsChain<NC + NCV, 6> ch;
-            ch.prefill(load);
-            ch.run(load, [&](int i, const Frag& a) {
-              if (i < NC) sacc = mfma32(a.v, knat[i].v, sacc);
-              else dpacc = mfma32(a.v, vnat[i - NC].v, dpacc);
-            });
-          }
-          // dV^T += dO^T P (steps 0..2*NEB-1), dK^T += Q^T dS (steps 2*NEB..): transposing reads
-          auto load_t = [&](int i) {
+        if (!wave_active || qb + BQ - 1 < kw0_in) return;  // block lies above this wave's keys
+        auto sd_load = [&](int sub) {
+          return [&, sub](int i) {
+            Frag a;
+            if (i < NC) a.u = *(const u32x4*)(smem + 32 * sub * QRB + qoff[i]);
+            else a.u = *(const u32x4*)(smem + 32 * sub * ORB + dooff[i - NC]);
+            return a;
+          };
+        };
+        auto sd_mma = [&](Sub& x) {
+          return [&](int i, const Frag& a) {
+            if (i < NC) x.s = mfma32(a.v, knat[i].v, x.s);
+            else x.dp = mfma32(a.v, vnat[i - NC].v, x.dp);
+          };
+        };
+        auto gr_load = [&](int sub) {
+          return [&, sub](int i) {
             Frag a;
             if (i < 2 * NEB) {
               const int eb = i % NEB, j = i / NEB;
-              const char* base = ot + (32 * sub + 16 * j) * ORB;
+              const char* base = smem + (32 * sub + 16 * j) * ORB;
               a.h[0] = lds_read_tr16(base + dotoff[0][eb]);
               a.h[1] = lds_read_tr16(base + dotoff[1][eb]);
             } else {
               const int db = (i - 2 * NEB) % NDB, j = (i - 2 * NEB) / NDB;
-              const char* base = qt + (32 * sub + 16 * j) * QRB;
+              const char* base = smem + (32 * sub + 16 * j) * QRB;
               a.h[0] = lds_read_tr16(base + qtoff[0][db]);
               a.h[1] = lds_read_tr16(base + qtoff[1][db]);
             }
             return a;
           };
-          LdsChain<2 * NEB + 2 * NDB, 6> ch2;
-          ch2.prefill(load_t);  // in flight during the exp / dS arithmetic
-          // accumulator element 4b+v <-> query q0 + 8b + 4hh + v, key column key_in
-          const bool need_mask = kw0_in + 31 > q0 || q0 + 31 >= s_len;
-          Frag pb[2], dsb[2];
+        };
+        auto gr_mma = [&](Sub& x) {
+          return [&](int i, const Frag& a) {
+            if (i < 2 * NEB) dvt[i % NEB] = mfma32(a.v, x.pb[i / NEB].v, dvt[i % NEB]);
+            else dkt[(i - 2 * NEB) % NDB] = mfma32(a.v, x.dsb[(i - 2 * NEB) / NDB].v, dkt[(i - 2 * NEB) % NDB]);
+          };
+        };
+        auto zero_sub = [&](Sub& x) {
 #pragma unroll
-          for (int b = 0; b < 4; ++b) {
-            const f32x4 l4 = *(const f32x4*)&lse_b[32 * sub + 8 * b + 4 * hh];
-            const f32x4 d4 = *(const f32x4*)&d_b[32 * sub + 8 * b + 4 * hh];
-            float pv[4], ds[4];
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-              float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[4 * b + v], p.scale_log2, -l4[v] * kLog2e));
-              if (need_mask) {
-                const int q_in = q0 + 8 * b + 4 * hh + v;
-                if (key_in > q_in || q_in >= s_len) pr = 0.f;
-              }
-              pv[v] = pr;
-              ds[v] = pr * (dpacc[4 * b + v] - d4[v]);
-            }
-            pb[b >> 1].w[2 * (b & 1)] = pack_bf16(pv[0], pv[1]);
-            pb[b >> 1].w[2 * (b & 1) + 1] = pack_bf16(pv[2], pv[3]);
-            dsb[b >> 1].w[2 * (b & 1)] = pack_bf16(ds[0], ds[1]);
-            dsb[b >> 1].w[2 * (b & 1) + 1] = pack_bf16(ds[2], ds[3]);
+          for (int i = 0; i < 16; ++i) x.s[i] = 0.f, x.dp[i] = 0.f;
+        };
+        // element i = 4b+v of the accumulators <-> query q0 + 8b + 4hh + v, key column key_in
+        f32x4 l4, d4;
+        float pr_prev = 0.f, ds_prev = 0.f;
+        auto sm_elem = [&](Sub& x, int sub, int i, auto masked) {
+          const int b = i >> 2, v = i & 3;
+          if (v == 0) {
+            l4 = *(const f32x4*)(smem + (32 * sub + 8 * b) * 4 + lseoff);
+            d4 = *(const f32x4*)(smem + (32 * sub + 8 * b) * 4 + dvoff);
           }
+          float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(x.s[i], p.scale_log2, -l4[v]));
+          if (decltype(masked)::value) {
+            const int q_in = qb + 32 * sub + 8 * b + 4 * hh + v;
+            if (key_in > q_in || q_in >= s_len) pr = 0.f;
+          }
+          const float ds = pr * (x.dp[i] - d4[v]);
+          if (i & 1) {
+            x.pb[b >> 1].w[2 * (b & 1) + (v >> 1)] = pack_bf16(pr_prev, pr);
+            x.dsb[b >> 1].w[2 * (b & 1) + (v >> 1)] = pack_bf16(ds_prev, ds);
+          } else {
+            pr_prev = pr;
+            ds_prev = ds;
+          }
+        };
+        auto run_single = [&](int sub) {
+          Sub x;
+          zero_sub(x);
+          LdsChain<NC + NCV, 4> c1;
+          c1.prefill(sd_load(sub));
+          c1.run(sd_load(sub), sd_mma(x));
+          LdsChain<2 * NEB + 2 * NDB, 4> c2;
+          c2.prefill(gr_load(sub));
+#pragma unroll
+          for (int i = 0; i < 16; ++i) sm_elem(x, sub, i, std::true_type{});
           __builtin_amdgcn_sched_barrier(0);
-          ch2.run(load_t, [&](int i, const Frag& a) {
-            if (i < 2 * NEB) dvt[i % NEB] = mfma32(a.v, pb[i / NEB].v, dvt[i % NEB]);
-            else dkt[(i - 2 * NEB) % NDB] = mfma32(a.v, dsb[(i - 2 * NEB) / NDB].v, dkt[(i - 2 * NEB) % NDB]);
-          });
+          c2.run(gr_load(sub), gr_mma(x));
+        };
+        auto run_pair = [&]() {
+          Sub xa, xb;
+          zero_sub(xa);
+          zero_sub(xb);
+          LdsChain<NC + NCV, 4> c1;
+          c1.prefill(sd_load(0));
+          c1.run(sd_load(0), sd_mma(xa));
+          c1.prefill(sd_load(1));
+          c1.template run_with<16>(sd_load(1), sd_mma(xb), [&](int i) { sm_elem(xa, 0, i, std::false_type{}); });
+          LdsChain<2 * NEB + 2 * NDB, 4> c2;
+          c2.prefill(gr_load(0));
+          c2.template run_with<16>(gr_load(0), gr_mma(xa), [&](int i) { sm_elem(xb, 1, i, std::false_type{}); });
+          c2.prefill(gr_load(1));
+          c2.run(gr_load(1), gr_mma(xb));
+        };
+        const bool need_a = qb + 31 >= kw0_in;                      // qb < s_len always holds
+        const bool need_b = qb + 63 >= kw0_in && qb + 32 < s_len;
+        const bool any_mask = kw0_in + 31 > qb || qb + 63 >= s_len;  // diagonal or sample tail in reach
+        if (need_a && need_b && !any_mask) {
+          run_pair();
+        } else {
+          if (need_a) run_single(0);
+          if (need_b) run_single(1);
         }
+      };
+
+      int cur_buf = 0;
+      for (int step = 0; step < n_steps; ++step) {
+        wait_async_loads();
+        __syncthreads();
+        if (step + 1 < n_steps) issue(step + 1);
+        if ((step & 1) != cur_buf) {  // point every LDS offset at this step's buffer
+          const int dq_ = (step & 1) ? Q_TILE : -Q_TILE, do_ = (step & 1) ? O_TILE : -O_TILE;
+          const int dr_ = (step & 1) ? BQ * 4 : -BQ * 4;
+#pragma unroll
+          for (int c = 0; c < NC; ++c) qoff[c] += dq_;
+#pragma unroll
+          for (int c = 0; c < NCV; ++c) dooff[c] += do_;
+#pragma unroll
+          for (int r = 0; r < 2; ++r) {
+#pragma unroll
+            for (int db = 0; db < NDB; ++db) qtoff[r][db] += dq_;
+#pragma unroll
+            for (int eb = 0; eb < NEB; ++eb) dotoff[r][eb] += do_;
+          }
+          lseoff += dr_;
+          dvoff += dr_;
+          cur_buf = step & 1;
+        }
+        do_step(step);
+      }
+      if (cur_buf) {  // leave the offsets on buffer 0 for the next item
+#pragma unroll
+        for (int c = 0; c < NC; ++c) qoff[c] -= Q_TILE;
+#pragma unroll
+        for (int c = 0; c < NCV; ++c) dooff[c] -= O_TILE;
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+#pragma unroll
+          for (int db = 0; db < NDB; ++db) qtoff[r][db] -= Q_TILE;
+#pragma unroll
+          for (int eb = 0; eb < NEB; ++eb) dotoff[r][eb] -= O_TILE;
+        }
+        lseoff -= BQ * 4;
+        dvoff -= BQ * 4;
       }
 
       if (key_valid) {
@@ -452,7 +540,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
   prof_write(pa, p.prof, tid);
 }
 
-// D[h,r] = sum_x dO[r,h,x] O[r,h,x]; resets both scheduler counters.
+// D[h,r] = sum_x dO[r,h,x] O[r,h,x], LSE2 = LSE*log2(e); resets both scheduler counters.
 template <int DV>
 __global__ __launch_bounds__(kThreads) void bwd_prepass_kernel(const BwdParams p) {
   constexpr int LPR = DV / 8;  // lanes per (row, head): 16 bytes of O and dO each
@@ -480,6 +568,7 @@ __global__ __launch_bounds__(kThreads) void bwd_prepass_kernel(const BwdParams p
     const int64_t r = rh / p.Hq;
     const int h = (int)(rh % p.Hq);
     p.D[(int64_t)h * p.T + r] = acc;
+    p.lse2[(int64_t)h * p.T + r] = p.lse[(int64_t)h * p.T + r] * kLog2e;
   }
 }
 

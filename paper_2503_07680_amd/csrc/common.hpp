@@ -113,6 +113,18 @@ __device__ __forceinline__ void async_copy16(const void* base_uniform, uint32_t 
       : "memory", "m0");
 }
 
+// 4-byte-per-lane variant: lane i writes LDS bytes [lds_addr + 4 i, +4).
+__device__ __forceinline__ void async_copy4(const void* base_uniform, uint32_t lane_byte_off,
+                                            uint32_t lds_addr_uniform) {
+  asm volatile(
+      "s_mov_b32 m0, %0\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dword %1, %2"
+      :
+      : "s"(lds_addr_uniform), "v"(lane_byte_off), "s"(base_uniform)
+      : "memory", "m0");
+}
+
 __device__ __forceinline__ uint32_t lds_address(const void* p) {
   return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
 }
@@ -180,6 +192,19 @@ struct LdsChain {
       mma(i, ring[i % PD]);
       if (i + PD < L) ring[i % PD] = load(i + PD);
       __builtin_amdgcn_sched_barrier(0);  // keep the read-ahead distance: no hoisting or sinking
+    }
+  }
+  // Same, with NS slices of independent vector arithmetic spread evenly behind the MFMAs: they
+  // execute in the MFMAs' shadow (the matrix pipe runs asynchronously to the issuing wave).
+  template <int NS, class Load, class Mma, class Slice>
+  __device__ __forceinline__ void run_with(Load load, Mma mma, Slice slice) {
+#pragma unroll
+    for (int i = 0; i < L; ++i) {
+      mma(i, ring[i % PD]);
+      if (i + PD < L) ring[i % PD] = load(i + PD);
+#pragma unroll
+      for (int sl = i * NS / L; sl < (i + 1) * NS / L; ++sl) slice(sl);
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
 };
@@ -274,7 +299,8 @@ struct BwdParams {
   const uint16_t *q, *k, *v, *o, *d_o;
   const float* lse;
   uint16_t *dq, *dk, *dv;
-  float* D;  // [Hq,T]
+  float* D;     // [Hq,T] rowsum(dO * O)
+  float* lse2;  // [Hq,T] LSE * log2(e)
   const int32_t* cu;
   const hbp_tile* tiles;    // key tiles (dK/dV kernel)
   const hbp_tile* q_tiles;  // query tiles (dQ kernel)
