@@ -339,12 +339,6 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
         for (int c = 0; c < NC; ++c) knat[c].u = key_valid ? *(const u32x4*)(kp + 16 * c) : u32x4{0, 0, 0, 0};
 #pragma unroll
         for (int c = 0; c < NCV; ++c) vnat[c].u = key_valid ? *(const u32x4*)(vp + 16 * c) : u32x4{0, 0, 0, 0};
-        // these fragments are only ever MFMA operands: park them in the accumulator register file
-        // so the vector file keeps room for the arithmetic (no copies: MFMA reads either file)
-#pragma unroll
-        for (int c = 0; c < NC; ++c) asm volatile("" : "+a"(knat[c].u));
-#pragma unroll
-        for (int c = 0; c < NCV; ++c) asm volatile("" : "+a"(vnat[c].u));
       }
       f32x16 dkt[NDB], dvt[NEB];
 #pragma unroll
@@ -380,8 +374,10 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
         };
         auto sd_mma = [&](Sub& x) {
           return [&](int i, const Frag& a) {
-            if (i < NC) x.s = mfma32(a.v, knat[i].v, x.s);
-            else x.dp = mfma32(a.v, vnat[i - NC].v, x.dp);
+            if (i == 0) x.s = mfma32_vgpr_first(a.v, knat[0].v);
+            else if (i < NC) mfma32_vgpr(x.s, a.v, knat[i].v);
+            else if (i == NC) x.dp = mfma32_vgpr_first(a.v, vnat[0].v);
+            else mfma32_vgpr(x.dp, a.v, vnat[i - NC].v);
           };
         };
         auto gr_load = [&](int sub) {
@@ -406,10 +402,6 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
             if (i < 2 * NEB) dvt[i % NEB] = mfma32(a.v, x.pb[i / NEB].v, dvt[i % NEB]);
             else dkt[(i - 2 * NEB) % NDB] = mfma32(a.v, x.dsb[(i - 2 * NEB) / NDB].v, dkt[(i - 2 * NEB) % NDB]);
           };
-        };
-        auto zero_sub = [&](Sub& x) {
-#pragma unroll
-          for (int i = 0; i < 16; ++i) x.s[i] = 0.f, x.dp[i] = 0.f;
         };
         // element i = 4b+v of the accumulators <-> query q0 + 8b + 4hh + v, key column key_in
         f32x4 l4, d4;
@@ -436,12 +428,12 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
         };
         auto run_single = [&](int sub) {
           Sub x;
-          zero_sub(x);
           LdsChain<NC + NCV, 4> c1;
           c1.prefill(sd_load(sub));
           c1.run(sd_load(sub), sd_mma(x));
           LdsChain<2 * NEB + 2 * NDB, 4> c2;
           c2.prefill(gr_load(sub));
+          mfma_results_ready(x.s, x.dp);
 #pragma unroll
           for (int i = 0; i < 16; ++i) sm_elem(x, sub, i, std::true_type{});
           __builtin_amdgcn_sched_barrier(0);
@@ -449,15 +441,15 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
         };
         auto run_pair = [&]() {
           Sub xa, xb;
-          zero_sub(xa);
-          zero_sub(xb);
           LdsChain<NC + NCV, 4> c1;
           c1.prefill(sd_load(0));
           c1.run(sd_load(0), sd_mma(xa));
           c1.prefill(sd_load(1));
+          mfma_results_ready(xa.s, xa.dp);
           c1.template run_with<16>(sd_load(1), sd_mma(xb), [&](int i) { sm_elem(xa, 0, i, std::false_type{}); });
           LdsChain<2 * NEB + 2 * NDB, 4> c2;
           c2.prefill(gr_load(0));
+          mfma_results_ready(xb.s, xb.dp);
           c2.template run_with<16>(gr_load(0), gr_mma(xa), [&](int i) { sm_elem(xb, 1, i, std::false_type{}); });
           c2.prefill(gr_load(1));
           c2.run(gr_load(1), gr_mma(xb));

@@ -25,6 +25,25 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 
+// The same MFMA with its accumulator forced into the vector register file.  In kernels that also
+// keep long-lived accumulators in the accumulation file the compiler would put EVERY MFMA result
+// there and copy it out element by element before any vector arithmetic; scores that feed exp()
+// right away are better produced in place.  Written as inline asm, so the wait states between an
+// MFMA result and its first vector read are the caller's duty: see mfma_results_ready().
+__device__ __forceinline__ f32x16 mfma32_vgpr_first(bf16x8 a, bf16x8 b) {
+  f32x16 d;
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "v"(b));
+  return d;
+}
+__device__ __forceinline__ void mfma32_vgpr(f32x16& c, bf16x8 a, bf16x8 b) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b));
+}
+// Orders every later read of x and y after 19 idle issue cycles that follow the MFMAs which
+// produced them (the longest wait the ISA asks for between a matrix result and a vector read).
+__device__ __forceinline__ void mfma_results_ready(f32x16& x, f32x16& y) {
+  asm volatile("s_nop 15\n\ts_nop 3" : "+v"(x), "+v"(y));
+}
+
 union Frag {
   bf16x8 v;
   u32x4 u;
