@@ -372,12 +372,30 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
             return a;
           };
         };
+        // The asm form (scores produced in the vector file) is only used where the kernel compiles
+        // without register spills: spill copies next to an asm MFMA would bypass the compiler's
+        // hazard handling.  d_qk = 192 spills, so it takes the builtin (slower, always safe).
+        constexpr bool kVgprScores = DQK <= 128;
         auto sd_mma = [&](Sub& x) {
           return [&](int i, const Frag& a) {
-            if (i == 0) x.s = mfma32_vgpr_first(a.v, knat[0].v);
-            else if (i < NC) mfma32_vgpr(x.s, a.v, knat[i].v);
-            else if (i == NC) x.dp = mfma32_vgpr_first(a.v, vnat[0].v);
-            else mfma32_vgpr(x.dp, a.v, vnat[i - NC].v);
+            if (kVgprScores) {
+              if (i == 0) x.s = mfma32_vgpr_first(a.v, knat[0].v);
+              else if (i < NC) mfma32_vgpr(x.s, a.v, knat[i].v);
+              else if (i == NC) x.dp = mfma32_vgpr_first(a.v, vnat[0].v);
+              else mfma32_vgpr(x.dp, a.v, vnat[i - NC].v);
+            } else {
+              if (i == 0 || i == NC) {
+                f32x16 z;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) z[e] = 0.f;
+                if (i == 0) x.s = mfma32(a.v, knat[0].v, z);
+                else x.dp = mfma32(a.v, vnat[0].v, z);
+              } else if (i < NC) {
+                x.s = mfma32(a.v, knat[i].v, x.s);
+              } else {
+                x.dp = mfma32(a.v, vnat[i - NC].v, x.dp);
+              }
+            }
           };
         };
         auto gr_load = [&](int sub) {
@@ -433,7 +451,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
           c1.run(sd_load(sub), sd_mma(x));
           LdsChain<2 * NEB + 2 * NDB, 4> c2;
           c2.prefill(gr_load(sub));
-          mfma_results_ready(x.s, x.dp);
+          if (kVgprScores) mfma_results_ready(x.s, x.dp);
 #pragma unroll
           for (int i = 0; i < 16; ++i) sm_elem(x, sub, i, std::true_type{});
           __builtin_amdgcn_sched_barrier(0);
@@ -445,11 +463,11 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
           c1.prefill(sd_load(0));
           c1.run(sd_load(0), sd_mma(xa));
           c1.prefill(sd_load(1));
-          mfma_results_ready(xa.s, xa.dp);
+          if (kVgprScores) mfma_results_ready(xa.s, xa.dp);
           c1.template run_with<16>(sd_load(1), sd_mma(xb), [&](int i) { sm_elem(xa, 0, i, std::false_type{}); });
           LdsChain<2 * NEB + 2 * NDB, 4> c2;
           c2.prefill(gr_load(0));
-          mfma_results_ready(xb.s, xb.dp);
+          if (kVgprScores) mfma_results_ready(xb.s, xb.dp);
           c2.template run_with<16>(gr_load(0), gr_mma(xa), [&](int i) { sm_elem(xb, 1, i, std::false_type{}); });
           c2.prefill(gr_load(1));
           c2.run(gr_load(1), gr_mma(xb));

@@ -165,19 +165,22 @@ struct TileLoader {
       rc[ii] = ((uint32_t)row << 16) | (uint32_t)(swz<D>(cpos, row) * 16);
     }
   }
-  // g: first row of the tile (wave-uniform); stride_bytes < 2^16 * ... fits 32 bits with row < ROWS
+  // One of this wave's PER_WAVE copy instructions (so a caller can spread them between other
+  // work: a burst of copies stalls the issuing wave behind the 64 B/clk address path).
+  // g: first row of the tile (wave-uniform); row * stride_bytes fits 32 bits.
+  __device__ __forceinline__ void issue_one(int ii, const uint16_t* g, uint32_t stride_bytes, int rows_valid,
+                                            const char* lds_tile, int wave) const {
+    const int inst = wave + 4 * ii;
+    if (N_INSTR % 4 != 0 && inst >= N_INSTR) return;
+    const uint32_t last = (uint32_t)(rows_valid - 1);
+    const uint32_t row = rc[ii] >> 16;
+    const uint32_t off = __umul24(row < last ? row : last, stride_bytes) + (rc[ii] & 0xffffu);
+    async_copy16(g, off, lds_address(lds_tile) + inst * 1024);
+  }
   __device__ __forceinline__ void issue(const uint16_t* g, uint32_t stride_bytes, int rows_valid,
                                         const char* lds_tile, int wave) const {
-    const uint32_t last = (uint32_t)(rows_valid - 1);
-    const uint32_t lds0 = lds_address(lds_tile);
 #pragma unroll
-    for (int ii = 0; ii < PER_WAVE; ++ii) {
-      const int inst = wave + 4 * ii;
-      if (N_INSTR % 4 != 0 && inst >= N_INSTR) break;
-      const uint32_t row = rc[ii] >> 16;
-      const uint32_t off = __umul24(row < last ? row : last, stride_bytes) + (rc[ii] & 0xffffu);
-      async_copy16(g, off, lds0 + inst * 1024);
-    }
+    for (int ii = 0; ii < PER_WAVE; ++ii) issue_one(ii, g, stride_bytes, rows_valid, lds_tile, wave);
   }
 };
 
