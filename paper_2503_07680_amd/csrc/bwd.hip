@@ -361,6 +361,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
         f32x16 s, dp;
         Frag pb[2], dsb[2];
       };
+      constexpr int kPD = 3;  // LDS read-ahead depth (fragments)
       auto do_step = [&](int step) {
         const int qb = qb_start + (step % nqb) * BQ;
         if (!wave_active || qb + BQ - 1 < kw0_in) return;  // block lies above this wave's keys
@@ -421,54 +422,80 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
             else dkt[(i - 2 * NEB) % NDB] = mfma32(a.v, x.dsb[(i - 2 * NEB) / NDB].v, dkt[(i - 2 * NEB) % NDB]);
           };
         };
-        // element i = 4b+v of the accumulators <-> query q0 + 8b + 4hh + v, key column key_in
-        f32x4 l4, d4;
-        float pr_prev = 0.f, ds_prev = 0.f;
-        auto sm_elem = [&](Sub& x, int sub, int i, auto masked) {
+        // element i = 4b+v of the accumulators <-> query q0 + 8b + 4hh + v, key column key_in.
+        // The per-element arithmetic  pr = exp2(c*s - lse2);  ds = pr * (dp - D)  is issued in two
+        // stages one slice apart (stage 1 of element i next to stage 2 of element i-1), so that no
+        // vector instruction waits on the one just before it; LSE2 / D of the 4 query rows of group
+        // b are read from LDS one group ahead (rows_prefetch(sub, 0) before the chain).
+        f32x4 l4, d4, l4n, d4n;
+        float e_cur = 0.f, d_prev = 0.f;      // exp of element i (stage 1), D of the element in stage 2
+        float pr_even = 0.f, ds_even = 0.f;
+        auto rows_prefetch = [&](int sub, int b) {
+          l4n = *(const f32x4*)(smem + (32 * sub + 8 * b) * 4 + lseoff);
+          d4n = *(const f32x4*)(smem + (32 * sub + 8 * b) * 4 + dvoff);
+        };
+        auto stage2 = [&](Sub& x, int sub, int i, float e_val, float d_val, auto masked) {
           const int b = i >> 2, v = i & 3;
-          if (v == 0) {
-            l4 = *(const f32x4*)(smem + (32 * sub + 8 * b) * 4 + lseoff);
-            d4 = *(const f32x4*)(smem + (32 * sub + 8 * b) * 4 + dvoff);
-          }
-          float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(x.s[i], p.scale_log2, -l4[v]));
+          float pr = e_val;
           if (decltype(masked)::value) {
             const int q_in = qb + 32 * sub + 8 * b + 4 * hh + v;
             if (key_in > q_in || q_in >= s_len) pr = 0.f;
           }
-          const float ds = pr * (x.dp[i] - d4[v]);
+          const float ds = pr * (x.dp[i] - d_val);
           if (i & 1) {
-            x.pb[b >> 1].w[2 * (b & 1) + (v >> 1)] = pack_bf16(pr_prev, pr);
-            x.dsb[b >> 1].w[2 * (b & 1) + (v >> 1)] = pack_bf16(ds_prev, ds);
+            x.pb[b >> 1].w[2 * (b & 1) + (v >> 1)] = pack_bf16(pr_even, pr);
+            x.dsb[b >> 1].w[2 * (b & 1) + (v >> 1)] = pack_bf16(ds_even, ds);
           } else {
-            pr_prev = pr;
-            ds_prev = ds;
+            pr_even = pr;
+            ds_even = ds;
           }
+        };
+        // slices 0..16: slice i runs stage 1 of element i (i < 16) and stage 2 of element i-1 (i > 0)
+        auto sm_slice = [&](Sub& x, int sub, int i, auto masked) {
+          const float e_prev = e_cur;
+          const float dd_prev = d_prev;
+          if (i < 16) {
+            const int b = i >> 2, v = i & 3;
+            if (v == 0) {
+              l4 = l4n;
+              d4 = d4n;
+              if (b < 3) rows_prefetch(sub, b + 1);
+            }
+            e_cur = __builtin_amdgcn_exp2f(__builtin_fmaf(x.s[i], p.scale_log2, -l4[v]));
+            d_prev = d4[v];
+          }
+          if (i > 0) stage2(x, sub, i - 1, e_prev, dd_prev, masked);
         };
         auto run_single = [&](int sub) {
           Sub x;
-          LdsChain<NC + NCV, 4> c1;
+          LdsChain<NC + NCV, kPD> c1;
           c1.prefill(sd_load(sub));
           c1.run(sd_load(sub), sd_mma(x));
-          LdsChain<2 * NEB + 2 * NDB, 4> c2;
+          LdsChain<2 * NEB + 2 * NDB, kPD> c2;
+          rows_prefetch(sub, 0);
           c2.prefill(gr_load(sub));
           if (kVgprScores) mfma_results_ready(x.s, x.dp);
 #pragma unroll
-          for (int i = 0; i < 16; ++i) sm_elem(x, sub, i, std::true_type{});
+          for (int i = 0; i < 17; ++i) sm_slice(x, sub, i, std::true_type{});
           __builtin_amdgcn_sched_barrier(0);
           c2.run(gr_load(sub), gr_mma(x));
         };
         auto run_pair = [&]() {
           Sub xa, xb;
-          LdsChain<NC + NCV, 4> c1;
+          LdsChain<NC + NCV, kPD> c1;
           c1.prefill(sd_load(0));
           c1.run(sd_load(0), sd_mma(xa));
+          rows_prefetch(0, 0);
           c1.prefill(sd_load(1));
           if (kVgprScores) mfma_results_ready(xa.s, xa.dp);
-          c1.template run_with<16>(sd_load(1), sd_mma(xb), [&](int i) { sm_elem(xa, 0, i, std::false_type{}); });
-          LdsChain<2 * NEB + 2 * NDB, 4> c2;
+          c1.template run_with<16>(sd_load(1), sd_mma(xb), [&](int i) { sm_slice(xa, 0, i, std::false_type{}); });
+          sm_slice(xa, 0, 16, std::false_type{});
+          LdsChain<2 * NEB + 2 * NDB, kPD> c2;
+          rows_prefetch(1, 0);
           c2.prefill(gr_load(0));
           if (kVgprScores) mfma_results_ready(xb.s, xb.dp);
-          c2.template run_with<16>(gr_load(0), gr_mma(xa), [&](int i) { sm_elem(xb, 1, i, std::false_type{}); });
+          c2.template run_with<16>(gr_load(0), gr_mma(xa), [&](int i) { sm_slice(xb, 1, i, std::false_type{}); });
+          sm_slice(xb, 1, 16, std::false_type{});
           c2.prefill(gr_load(1));
           c2.run(gr_load(1), gr_mma(xb));
         };
