@@ -17,97 +17,128 @@
 
 namespace hbp {
 
-// One key tile (64 keys) for one wavefront (32 query rows).  MASKED: the tile reaches past the
-// wave's first query row, so the causal compare is applied; interior tiles skip it entirely.
-// LDS operand reads run PD fragments ahead of the MFMAs that consume them.
+// One key tile (64 keys = two blocks of 32) for one wavefront (32 query rows).  MASKED: the tile
+// reaches past the wave's first query row, so the causal compare is applied; interior tiles skip it.
+//
+// Each 32-key block is one online-softmax step.  The two blocks are software-pipelined inside the
+// wave so that the softmax arithmetic of a block is issued, a few instructions at a time, behind the
+// MFMAs of the neighbouring product (a vector instruction only overlaps MFMAs of its own wave, and
+// only a handful fit behind each):
+//     S(0) | S(1) + softmax(0) | PV(0) + softmax(1) | PV(1)
+// LDS operand reads run PD fragments ahead of the MFMAs that consume them.  koff / voff are byte
+// offsets from `lds` that already contain the current buffer's base.
 template <int DQK, int DV, bool MASKED>
-__device__ __forceinline__ void fwd_tile(const char* kt_lds, const char* vt_lds, const int (&koff)[DQK / 16],
+__device__ __forceinline__ void fwd_tile(const char* lds, const int (&koff)[DQK / 16],
                                          const int (&voff)[2][DV / 32], const Frag (&qf)[DQK / 16],
                                          f32x16 (&oacc)[DV / 32], float& m_run, float& l_run,
                                          float scale_log2, int k_off, int q_in, int hh) {
   constexpr int KRB = DQK * 2, VRB = DV * 2;
   constexpr int NC = DQK / 16, NEB = DV / 32;
   constexpr int PD = 4;
+  constexpr int NSL = 18;  // softmax slices per block: 0 = row max, 1..16 = elements, 17 = drain
 
-  f32x16 sacc[2];
+  f32x16 s[2];
+  Frag pf[2][2];  // [blk][j]
 #pragma unroll
   for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) sacc[blk][i] = 0.f;
-  {
-    constexpr int L = 2 * NC;
-    Frag ring[PD];
-#pragma unroll
-    for (int i = 0; i < PD; ++i) ring[i].u = *(const u32x4*)(kt_lds + 32 * (i / NC) * KRB + koff[i % NC]);
-#pragma unroll
-    for (int i = 0; i < L; ++i) {
-      sacc[i / NC] = mfma32(ring[i % PD].v, qf[i % NC].v, sacc[i / NC]);
-      if (i + PD < L)
-        ring[i % PD].u = *(const u32x4*)(kt_lds + 32 * ((i + PD) / NC) * KRB + koff[(i + PD) % NC]);
-      __builtin_amdgcn_sched_barrier(0);  // keep the read-ahead distance: no hoisting of later reads
-    }
-  }
-  // first V fragments: their LDS latency hides under the softmax arithmetic
-  constexpr int LV = 4 * NEB;  // steps (blk, j, eb), eb fastest
-  Frag vring[PD];
-  auto load_v = [&](int i) {
-    const int eb = i % NEB, bj = i / NEB;  // bj = 2*blk + j
-    const char* base = vt_lds + 16 * bj * VRB;
-    Frag f;
-    f.h[0] = lds_read_tr16(base + voff[0][eb]);
-    f.h[1] = lds_read_tr16(base + voff[1][eb]);
-    return f;
+    for (int i = 0; i < 16; ++i) s[blk][i] = 0.f;
+
+  auto k_load = [&](int blk) {
+    return [&, blk](int c) {
+      Frag f;
+      f.u = *(const u32x4*)(lds + 32 * blk * KRB + koff[c]);
+      return f;
+    };
   };
-#pragma unroll
-  for (int i = 0; i < PD; ++i) vring[i] = load_v(i);
-  __builtin_amdgcn_sched_barrier(0);
+  auto s_mma = [&](int blk) {
+    return [&, blk](int c, const Frag& f) { s[blk] = mfma32(f.v, qf[c].v, s[blk]); };
+  };
+  auto v_load = [&](int blk) {  // step (j, eb), eb fastest
+    return [&, blk](int i) {
+      const int eb = i % NEB, j = i / NEB;
+      const char* base = lds + (32 * blk + 16 * j) * VRB;
+      Frag f;
+      f.h[0] = lds_read_tr16(base + voff[0][eb]);
+      f.h[1] = lds_read_tr16(base + voff[1][eb]);
+      return f;
+    };
+  };
+  auto pv_mma = [&](int blk) {
+    return [&, blk](int i, const Frag& f) { oacc[i % NEB] = mfma32(f.v, pf[blk][i / NEB].v, oacc[i % NEB]); };
+  };
 
-  float mx = -INFINITY;
+  // softmax of one block, cut in slices.  Elements go through two stages one slice apart (exp of
+  // element e next to the sum/pack of element e-1) so no instruction waits on its predecessor.
+  float p_cur = 0.f, p_even = 0.f, psum = 0.f, alpha_deferred = 1.f;
+  bool rescale_deferred = false;
+  auto sm_slice = [&](int blk, int sl, bool defer_o_rescale) {
+    if (sl == 0) {
+      float mx = -INFINITY;
+      // element i holds key k_off + 32 blk + 4 hh + (8 (i>>2) + (i&3)): masked iff that constant
+      // exceeds d.  d is kept opaque so the compare stays "constant vs one register" instead of
+      // sixteen precomputed per-lane thresholds held across the whole loop.
+      int d = q_in - (k_off + 32 * blk + 4 * hh);
+      if (MASKED) asm volatile("" : "+v"(d));
 #pragma unroll
-  for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      if (MASKED) {
-        const int key_in = k_off + 32 * blk + 8 * (i >> 2) + 4 * hh + (i & 3);
-        if (key_in > q_in) sacc[blk][i] = -INFINITY;
+      for (int i = 0; i < 16; ++i) {
+        if (MASKED) {
+          if (8 * (i >> 2) + (i & 3) > d) s[blk][i] = -INFINITY;
+        }
+        mx = fmaxf(mx, s[blk][i]);
       }
-      mx = fmaxf(mx, sacc[blk][i]);
+      mx = max_with_other_half(mx) * scale_log2;  // scale > 0: max commutes with the scaling
+      // Lazy rescale: the running reference m_run only moves when some row's maximum grew by more
+      // than 2^8; until then probabilities are taken relative to the old reference (they stay
+      // below 2^8, and O and l share the reference, so the result is unchanged).
+      if (__builtin_amdgcn_ballot_w64(mx > m_run + 8.0f) != 0) {
+        const float m_new = fmaxf(m_run, mx);  // finite: key 0 of the sample is visible to every row
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        m_run = m_new;
+        l_run *= alpha;
+        if (defer_o_rescale) {  // O is being accumulated by MFMAs in flight: scale it after them
+          alpha_deferred = alpha;
+          rescale_deferred = true;
+        } else {
+#pragma unroll
+          for (int eb = 0; eb < NEB; ++eb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) oacc[eb][i] *= alpha;
+        }
+      }
+      psum = 0.f;
+      return;
     }
-  mx = max_with_other_half(mx) * scale_log2;  // scale > 0: max commutes with the scaling
-  // Lazy rescale: the running reference m_run only moves when some row's maximum grew by more
-  // than 2^8; until then probabilities are taken relative to the old reference (they stay below
-  // 2^8, exact in fp32/bf16 range, and O and l use the same reference so the result is unchanged).
-  if (__builtin_amdgcn_ballot_w64(mx > m_run + 8.0f) != 0) {
-    const float m_new = fmaxf(m_run, mx);  // finite: key 0 of the sample is visible to every row
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-    m_run = m_new;
-    l_run *= alpha;
+    const float p_prev = p_cur;
+    if (sl <= 16) {
+      const int e = sl - 1;
+      p_cur = __builtin_amdgcn_exp2f(__builtin_fmaf(s[blk][e], scale_log2, -m_run));
+    }
+    if (sl >= 2) {
+      const int e = sl - 2;  // element whose exp was issued one slice ago
+      psum += p_prev;        // unrounded: LSE must not inherit the bf16 rounding of P
+      if (e & 1) pf[blk][e >> 3].w[(e & 7) >> 1] = pack_bf16(p_even, p_prev);
+      else p_even = p_prev;
+    }
+    if (sl == NSL - 1) l_run += psum;
+  };
+
+  LdsChain<NC, PD> cs;
+  cs.prefill(k_load(0));
+  cs.run(k_load(0), s_mma(0));
+  cs.prefill(k_load(1));
+  cs.template run_with<NSL>(k_load(1), s_mma(1), [&](int sl) { sm_slice(0, sl, false); });
+  LdsChain<2 * NEB, PD> cv;
+  cv.prefill(v_load(0));
+  cv.template run_with<NSL>(v_load(0), pv_mma(0), [&](int sl) { sm_slice(1, sl, true); });
+  cv.prefill(v_load(1));
+  if (rescale_deferred) {
 #pragma unroll
     for (int eb = 0; eb < NEB; ++eb)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) oacc[eb][i] *= alpha;
+      for (int i = 0; i < 16; ++i) oacc[eb][i] *= alpha_deferred;
   }
-  Frag pf[4];  // index 2*blk + j
-  float psum = 0.f;
-#pragma unroll
-  for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[blk][8 * j + 2 * w], scale_log2, -m_run));
-        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[blk][8 * j + 2 * w + 1], scale_log2, -m_run));
-        pf[2 * blk + j].w[w] = pack_bf16(p0, p1);
-        psum += p0 + p1;  // unrounded: LSE must not inherit the bf16 rounding of P
-      }
-  l_run += psum;
-  __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-  for (int i = 0; i < LV; ++i) {
-    oacc[i % NEB] = mfma32(vring[i % PD].v, pf[i / NEB].v, oacc[i % NEB]);
-    if (i + PD < LV) vring[i % PD] = load_v(i + PD);
-    __builtin_amdgcn_sched_barrier(0);
-  }
+  cv.run(v_load(1), pv_mma(1));
 }
 
 template <int DQK, int DV>
@@ -140,7 +171,7 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(const FwdParams p) {
 #pragma unroll
       for (int eb = 0; eb < NEB; ++eb) {
         const int c = 4 * eb + 2 * (G & 1) + ((s & 3) >> 1);
-        voff[r][eb] = (8 * r + k8) * VRB + swz<DV>(c, 8 * r + k8) * 16 + (s & 1) * 8;
+        voff[r][eb] = 2 * K_TILE + (8 * r + k8) * VRB + swz<DV>(c, 8 * r + k8) * 16 + (s & 1) * 8;
       }
   }
   TileLoader<DQK, BN> k_loader;
@@ -212,20 +243,37 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(const FwdParams p) {
       float m_run = -INFINITY, l_run = 0.f;
       const int q_in = qw0 + l32;
 
-      for (int kt = 0; kt < nkt; ++kt) {
+      int cur_buf = 0;
+      auto point_offsets_at = [&](int buf) {  // move every LDS offset to the other buffer
+        const int dk = buf ? K_TILE : -K_TILE, dv = buf ? V_TILE : -V_TILE;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) koff[c] += dk;
+#pragma unroll
+        for (int r = 0; r < 2; ++r)
+#pragma unroll
+          for (int eb = 0; eb < NEB; ++eb) voff[r][eb] += dv;
+        cur_buf = buf;
+      };
+      auto begin_tile = [&](int kt) {
         wait_async_loads();
         __syncthreads();  // tile kt has landed for every wave; tile kt-1 is no longer read
         if (kt + 1 < nkt) issue(kt + 1);
-
-        const int k_off = kt * BN;
-        if (!wave_active || k_off > qw0 + 31) continue;  // nothing at or below the diagonal
-        const char* kt_lds = k_lds + (kt & 1) * K_TILE;
-        const char* vt_lds = v_lds + (kt & 1) * V_TILE;
-        if (k_off + BN - 1 > qw0)
-          fwd_tile<DQK, DV, true>(kt_lds, vt_lds, koff, voff, qf, oacc, m_run, l_run, p.scale_log2, k_off, q_in, hh);
-        else
-          fwd_tile<DQK, DV, false>(kt_lds, vt_lds, koff, voff, qf, oacc, m_run, l_run, p.scale_log2, k_off, q_in, hh);
+        if ((kt & 1) != cur_buf) point_offsets_at(kt & 1);
+      };
+      // Interior tiles (entirely below this wave's first query row) and diagonal tiles run in two
+      // separate loops, one code variant each; every wave still passes nkt barriers in total.
+      const int n_interior = wave_active ? min(nkt, (qw0 + 1) / BN) : 0;
+      int kt = 0;
+      for (; kt < n_interior; ++kt) {
+        begin_tile(kt);
+        fwd_tile<DQK, DV, false>(smem, koff, voff, qf, oacc, m_run, l_run, p.scale_log2, kt * BN, q_in, hh);
       }
+      for (; kt < nkt; ++kt) {
+        begin_tile(kt);
+        if (wave_active && kt * BN <= qw0 + 31)  // else: nothing at or below the diagonal
+          fwd_tile<DQK, DV, true>(smem, koff, voff, qf, oacc, m_run, l_run, p.scale_log2, kt * BN, q_in, hh);
+      }
+      if (cur_buf) point_offsets_at(0);
 
       // finalise: O = acc / l, LSE = (m + log2 l) * ln 2
       const float l_tot = l_run + xor32(l_run);
