@@ -57,13 +57,17 @@ __device__ __forceinline__ void prof_write(const ProfAcc& a, hbp_profile_rec* pr
 
 // ------------------------------------------------------------------------------------- dQ
 template <int DQK, int DV>
-__global__ __launch_bounds__(kThreads, (DQK > 128 ? 1 : 2)) void bwd_dq_kernel(const BwdParams p) {
+__global__ __launch_bounds__(kThreads, 1) void bwd_dq_kernel(const BwdParams p) {
   constexpr int BM = 128, BN = 64;
   constexpr int KRB = DQK * 2, VRB = DV * 2;
   constexpr int K_TILE = BN * KRB, V_TILE = BN * VRB;
   constexpr int NC = DQK / 16, NCV = DV / 16, NDB = DQK / 32;
+  constexpr int PD = 4;
+  // Scores in the vector file (asm MFMA) only where the kernel compiles without spills.
+  constexpr bool kVgprScores = DQK <= 128;
 
   extern __shared__ __attribute__((aligned(1024))) char smem[];
+  // [K buf0][K buf1][V buf0][V buf1]
   char* const k_lds = smem;
   char* const v_lds = smem + 2 * K_TILE;
 
@@ -71,11 +75,12 @@ __global__ __launch_bounds__(kThreads, (DQK > 128 ? 1 : 2)) void bwd_dq_kernel(c
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
 
+  // LDS byte offsets from smem; they contain the current buffer's base (toggled once per tile)
   int koff[NC], vnoff[NCV], ktoff[2][NDB];
 #pragma unroll
   for (int c = 0; c < NC; ++c) koff[c] = l32 * KRB + swz<DQK>(2 * c + hh, l32) * 16;
 #pragma unroll
-  for (int c = 0; c < NCV; ++c) vnoff[c] = l32 * VRB + swz<DV>(2 * c + hh, l32) * 16;
+  for (int c = 0; c < NCV; ++c) vnoff[c] = 2 * K_TILE + l32 * VRB + swz<DV>(2 * c + hh, l32) * 16;
   {
     const int G = lane >> 4, s = lane & 15;
     const int k8 = 4 * hh + (s >> 2);
@@ -150,68 +155,155 @@ __global__ __launch_bounds__(kThreads, (DQK > 128 ? 1 : 2)) void bwd_dq_kernel(c
       for (int db = 0; db < NDB; ++db)
 #pragma unroll
         for (int i = 0; i < 16; ++i) dqacc[db][i] = 0.f;
+      const int q_in = qw0 + l32;
 
-      for (int kt = 0; kt < nkt; ++kt) {
+      // One 32-key block: sd = (S^T, dP^T) products, sm = dS^T = exp2(c S^T - LSE2)(dP^T - D),
+      // gr = dQ^T += K^T dS^T.  Interior tiles pipeline their two blocks inside the wave:
+      //     sd(0) | sd(1) + sm(0) | gr(0) + sm(1) first half | gr(1) first half + sm(1) rest | gr(1) rest
+      struct Blk {
+        f32x16 s, dp;
+        Frag dsf[2];
+      };
+      auto sd_load = [&](int blk) {
+        return [&, blk](int i) {
+          Frag a;
+          if (i < NC) a.u = *(const u32x4*)(smem + 32 * blk * KRB + koff[i]);
+          else a.u = *(const u32x4*)(smem + 32 * blk * VRB + vnoff[i - NC]);
+          return a;
+        };
+      };
+      auto sd_mma = [&](Blk& x) {
+        return [&](int i, const Frag& a) {
+          if (kVgprScores) {
+            if (i == 0) x.s = mfma32_vgpr_first(a.v, qf[0].v);
+            else if (i < NC) mfma32_vgpr(x.s, a.v, qf[i].v);
+            else if (i == NC) x.dp = mfma32_vgpr_first(a.v, dof[0].v);
+            else mfma32_vgpr(x.dp, a.v, dof[i - NC].v);
+          } else {
+            if (i == 0 || i == NC) {
+              f32x16 z;
+#pragma unroll
+              for (int e = 0; e < 16; ++e) z[e] = 0.f;
+              if (i == 0) x.s = mfma32(a.v, qf[0].v, z);
+              else x.dp = mfma32(a.v, dof[0].v, z);
+            } else if (i < NC) {
+              x.s = mfma32(a.v, qf[i].v, x.s);
+            } else {
+              x.dp = mfma32(a.v, dof[i - NC].v, x.dp);
+            }
+          }
+        };
+      };
+      auto gr_frag = [&](int blk, int j, int db) {
+        const char* base = smem + (32 * blk + 16 * j) * KRB;
+        Frag a;
+        a.h[0] = lds_read_tr16(base + ktoff[0][db]);
+        a.h[1] = lds_read_tr16(base + ktoff[1][db]);
+        return a;
+      };
+      // slices 0..16 of a block: slice k issues exp for element k (k < 16) and finishes element
+      // k-1 (k > 0); element e = 4b+v <-> key 32 blk + 8b + 4hh + v of the tile, query column q_in
+      float e_cur = 0.f, ds_even = 0.f;
+      auto sm_slice = [&](Blk& x, int kb, int k, auto masked) {
+        const float e_prev = e_cur;
+        if (k < 16) e_cur = __builtin_amdgcn_exp2f(__builtin_fmaf(x.s[k], p.scale_log2, -lse2));
+        if (k > 0) {
+          const int e = k - 1;
+          float pr = e_prev;
+          if (decltype(masked)::value) {
+            if (kb + 8 * (e >> 2) + 4 * hh + (e & 3) > q_in) pr = 0.f;
+          }
+          const float ds = pr * (x.dp[e] - Dv);
+          if (e & 1) x.dsf[e >> 3].w[(e & 7) >> 1] = pack_bf16(ds_even, ds);
+          else ds_even = ds;
+        }
+      };
+
+      int cur_buf = 0;
+      auto point_offsets_at = [&](int buf) {
+        const int dk = buf ? K_TILE : -K_TILE, dv = buf ? V_TILE : -V_TILE;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) koff[c] += dk;
+#pragma unroll
+        for (int c = 0; c < NCV; ++c) vnoff[c] += dv;
+#pragma unroll
+        for (int r = 0; r < 2; ++r)
+#pragma unroll
+          for (int db = 0; db < NDB; ++db) ktoff[r][db] += dk;
+        cur_buf = buf;
+      };
+      auto begin_tile = [&](int kt) {
         wait_async_loads();
         __syncthreads();
         if (kt + 1 < nkt) issue(kt + 1);
+        if ((kt & 1) != cur_buf) point_offsets_at(kt & 1);
+      };
+
+      const int n_interior = wave_active ? min(nkt, (qw0 + 1) / BN) : 0;
+      int kt = 0;
+      for (; kt < n_interior; ++kt) {
+        begin_tile(kt);
+        const int k_off = kt * BN;
+        Blk x0, x1;
+        LdsChain<NC + NCV, PD> c1;
+        c1.prefill(sd_load(0));
+        c1.run(sd_load(0), sd_mma(x0));
+        c1.prefill(sd_load(1));
+        if (kVgprScores) mfma_results_ready(x0.s, x0.dp);
+        c1.template run_with<17>(sd_load(1), sd_mma(x1), [&](int k) { sm_slice(x0, k_off, k, std::false_type{}); });
+        // gr(0) (2*NDB MFMAs) then gr(1) j=0 (NDB) then gr(1) j=1 (NDB), with sm(1) spread so that
+        // dS chunk j of block 1 is complete before the MFMAs that read it
+        constexpr int LG = 4 * NDB;
+        auto g_load = [&](int i) {
+          const int blk = i / (2 * NDB), j = (i / NDB) & 1, db = i % NDB;
+          return gr_frag(blk, j, db);
+        };
+        LdsChain<LG, PD> c2;
+        c2.prefill(g_load);
+        if (kVgprScores) mfma_results_ready(x1.s, x1.dp);
+#pragma unroll
+        for (int i = 0; i < LG; ++i) {
+          const int blk = i / (2 * NDB), j = (i / NDB) & 1, db = i % NDB;
+          Blk& x = blk ? x1 : x0;
+          dqacc[db] = mfma32(c2.ring[i % PD].v, x.dsf[j].v, dqacc[db]);
+          if (i + PD < LG) c2.ring[i % PD] = g_load(i + PD);
+          // sm(1): slices 0..8 behind gr(0) (chunk 0 of block 1 done), 9..16 behind gr(1) j=0
+          constexpr int A = 2 * NDB, B = NDB;
+          if (i < A) {
+#pragma unroll
+            for (int k = i * 9 / A; k < (i + 1) * 9 / A; ++k) sm_slice(x1, k_off + 32, k, std::false_type{});
+          } else if (i < A + B) {
+#pragma unroll
+            for (int k = 9 + (i - A) * 8 / B; k < 9 + (i - A + 1) * 8 / B; ++k)
+              sm_slice(x1, k_off + 32, k, std::false_type{});
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      for (; kt < nkt; ++kt) {  // tiles that touch the diagonal: plain masked path, block by block
+        begin_tile(kt);
         const int k_off = kt * BN;
         if (!wave_active || k_off > qw0 + 31) continue;
-        const char* kt_lds = k_lds + (kt & 1) * K_TILE;
-        const char* vt_lds = v_lds + (kt & 1) * V_TILE;
-        const int q_in = qw0 + l32;
 #pragma unroll
         for (int blk = 0; blk < 2; ++blk) {
           const int kb = k_off + 32 * blk;
           if (kb > qw0 + 31) continue;
-          f32x16 sacc, dpacc;
+          Blk x;
+          LdsChain<NC + NCV, PD> c1;
+          c1.prefill(sd_load(blk));
+          c1.run(sd_load(blk), sd_mma(x));
+          auto g_load = [&](int i) { return gr_frag(blk, i / NDB, i % NDB); };
+          LdsChain<2 * NDB, PD> c2;
+          c2.prefill(g_load);
+          if (kVgprScores) mfma_results_ready(x.s, x.dp);
 #pragma unroll
-          for (int i = 0; i < 16; ++i) sacc[i] = 0.f, dpacc[i] = 0.f;
-          {
-            // S^T = K Q^T (steps 0..NC-1) and dP^T = V dO^T (steps NC..NC+NCV-1), one read pipeline
-            auto load = [&](int i) {
-              Frag a;
-              if (i < NC) a.u = *(const u32x4*)(kt_lds + 32 * blk * KRB + koff[i]);
-              else a.u = *(const u32x4*)(vt_lds + 32 * blk * VRB + vnoff[i - NC]);
-              return a;
-            };
-            LdsChain<NC + NCV, 4> ch;
-            ch.prefill(load);
-            ch.run(load, [&](int i, const Frag& a) {
-              if (i < NC) sacc = mfma32(a.v, qf[i].v, sacc);
-              else dpacc = mfma32(a.v, dof[i - NC].v, dpacc);
-            });
-          }
-          auto load_kt = [&](int i) {  // step (j, db), db fastest
-            const int db = i % NDB, j = i / NDB;
-            const char* base = kt_lds + (32 * blk + 16 * j) * KRB;
-            Frag a;
-            a.h[0] = lds_read_tr16(base + ktoff[0][db]);
-            a.h[1] = lds_read_tr16(base + ktoff[1][db]);
-            return a;
-          };
-          LdsChain<2 * NDB, 4> ch2;
-          ch2.prefill(load_kt);  // in flight during the exp / dS arithmetic
-          const bool need_mask = kb + 31 > qw0;
-          Frag dsf[2];
-#pragma unroll
-          for (int b = 0; b < 4; ++b) {
-            float ds[4];
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-              float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[4 * b + v], p.scale_log2, -lse2));
-              if (need_mask && kb + 8 * b + 4 * hh + v > q_in) pr = 0.f;
-              ds[v] = pr * (dpacc[4 * b + v] - Dv);
-            }
-            dsf[b >> 1].w[2 * (b & 1)] = pack_bf16(ds[0], ds[1]);
-            dsf[b >> 1].w[2 * (b & 1) + 1] = pack_bf16(ds[2], ds[3]);
-          }
+          for (int k = 0; k < 17; ++k) sm_slice(x, kb, k, std::true_type{});
           __builtin_amdgcn_sched_barrier(0);
-          ch2.run(load_kt, [&](int i, const Frag& a) {
-            dqacc[i % NDB] = mfma32(a.v, dsf[i / NDB].v, dqacc[i % NDB]);
-          });
+          c2.run(g_load, [&](int i, const Frag& a) { dqacc[i % NDB] = mfma32(a.v, x.dsf[i / NDB].v, dqacc[i % NDB]); });
         }
       }
+      if (cur_buf) point_offsets_at(0);
+
       if (row_valid) {
         uint16_t* dqp = p.dq + (int64_t)my_row * p.q_st + (int64_t)h * p.q_sh + 4 * hh;
 #pragma unroll
