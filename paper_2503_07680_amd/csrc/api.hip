@@ -164,8 +164,7 @@ extern "C" hbp_status hbp_varlen_attn_fwd(const hbp_attn_desc* desc, const void*
 
   hipStream_t hs = static_cast<hipStream_t>(stream);
   if (hbp::launch_zero_counters(p.counter, hs) != 0) return HBP_ERR_DEVICE;
-  const int grid = grid_for((int64_t)n_q_tiles * p.Hq, 2);
-  if (hbp::launch_fwd(desc->d_qk, desc->d_v, p, grid, hs, g_events[HBP_FWD][0], g_events[HBP_FWD][1]) != 0) return HBP_ERR_DEVICE;
+  if (hbp::launch_fwd(desc->d_qk, desc->d_v, p, kNumCU, hs, g_events[HBP_FWD][0], g_events[HBP_FWD][1]) != 0) return HBP_ERR_DEVICE;
   return HBP_OK;
 }
 

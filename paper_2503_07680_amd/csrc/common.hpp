@@ -184,6 +184,57 @@ struct TileLoader {
   }
 };
 
+// The same copy with the per-lane source offsets of a FULL tile (all ROWS rows valid) kept ready, so
+// that such a copy costs no vector arithmetic at all and can be dropped between MFMAs one at a time.
+// A tile with fewer valid rows recomputes its (clamped) offsets from the lane id.
+template <int D, int ROWS, int NW = 4>
+struct FullTileLoader {
+  static constexpr int RB = D * 2;
+  static constexpr int N_INSTR = ROWS * RB / 1024;
+  static constexpr int PER_WAVE = (N_INSTR + NW - 1) / NW;  // NW waves share the tile's copies
+  uint32_t off[PER_WAVE];  // row * stride_bytes + byte offset of the source chunk inside its row
+
+  static __device__ __forceinline__ bool has(int ii, int wave) { return N_INSTR % NW == 0 || wave + NW * ii < N_INSTR; }
+  __device__ __forceinline__ void init(int wave, int lane, uint32_t stride_bytes) {
+#pragma unroll
+    for (int ii = 0; ii < PER_WAVE; ++ii) {
+      const int pos = (wave + NW * ii) * 1024 + lane * 16;
+      const int row = pos / RB, cpos = (pos % RB) / 16;
+      off[ii] = (uint32_t)row * stride_bytes + (uint32_t)(swz<D>(cpos, row) * 16);
+    }
+  }
+  // copy ii of this wave, every row of the tile valid
+  __device__ __forceinline__ void issue_full(int ii, const uint16_t* g, const char* lds_tile, int wave) const {
+    if (!has(ii, wave)) return;
+    async_copy16(g, off[ii], lds_address(lds_tile) + (wave + NW * ii) * 1024);
+  }
+  // copy ii of this wave, rows >= rows_valid re-read the last valid row
+  __device__ __forceinline__ void issue_clamped(int ii, const uint16_t* g, uint32_t stride_bytes, int rows_valid,
+                                                const char* lds_tile, int wave, int lane) const {
+    if (!has(ii, wave)) return;
+    const int pos = (wave + NW * ii) * 1024 + lane * 16;
+    const int row = pos / RB, cpos = (pos % RB) / 16;
+    const int last = rows_valid - 1;
+    const uint32_t o = (uint32_t)(row < last ? row : last) * stride_bytes + (uint32_t)(swz<D>(cpos, row) * 16);
+    async_copy16(g, o, lds_address(lds_tile) + (wave + NW * ii) * 1024);
+  }
+  __device__ __forceinline__ void issue_one(int ii, const uint16_t* g, uint32_t stride_bytes, int rows_valid,
+                                            const char* lds_tile, int wave, int lane) const {
+    if (rows_valid >= ROWS) issue_full(ii, g, lds_tile, wave);
+    else issue_clamped(ii, g, stride_bytes, rows_valid, lds_tile, wave, lane);
+  }
+  __device__ __forceinline__ void issue(const uint16_t* g, uint32_t stride_bytes, int rows_valid,
+                                        const char* lds_tile, int wave, int lane) const {
+    if (rows_valid >= ROWS) {
+#pragma unroll
+      for (int ii = 0; ii < PER_WAVE; ++ii) issue_full(ii, g, lds_tile, wave);
+    } else {
+#pragma unroll
+      for (int ii = 0; ii < PER_WAVE; ++ii) issue_clamped(ii, g, stride_bytes, rows_valid, lds_tile, wave, lane);
+    }
+  }
+};
+
 // all of this wave's outstanding global loads (including global -> LDS copies) have completed
 __device__ __forceinline__ void wait_async_loads() {
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0), expcnt and lgkmcnt left at their maxima
@@ -193,6 +244,11 @@ __device__ __forceinline__ void wait_async_loads() {
 // words addressed by lanes i/4, i/4+4, i/4+8, i/4+12 of the group.
 __device__ __forceinline__ s16x4 lds_read_tr16(const char* addr) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)addr);
+}
+
+// the same read from an absolute LDS address held as an integer
+__device__ __forceinline__ s16x4 lds_read_tr16_at(uint32_t lds_addr) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(uintptr_t)lds_addr);
 }
 
 // A chain of L MFMAs whose A operands come from LDS, with the reads running PD fragments ahead of
@@ -335,7 +391,8 @@ struct BwdParams {
 
 // launchers implemented in the .hip files; return hipError_t as int
 // ev0/ev1: optional events recorded around the persistent main kernel
-int launch_fwd(int d_qk, int d_v, const FwdParams& p, int grid, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
+// n_cu: compute units to fill (the kernel picks its own workgroup shape and grid)
+int launch_fwd(int d_qk, int d_v, const FwdParams& p, int n_cu, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
 // ev: {dkdv start, dkdv stop, dq start, dq stop}, entries may be null
 int launch_bwd(int d_qk, int d_v, const BwdParams& p, int grid_dq, int grid_dkdv, hipStream_t s, hipEvent_t* ev);
 int launch_zero_counters(int32_t* counters, hipStream_t s);  // the kNumXcd forward counters

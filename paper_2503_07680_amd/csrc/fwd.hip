@@ -1,168 +1,276 @@
 // Forward kernel: causal attention inside each sample of a packed buffer, gfx950.
 //
 // One work item = (query tile of <=128 rows, query head).  A persistent grid takes items from
-// an atomic counter in worklist order (longest causal cost first).  Per item the workgroup
-// (4 wavefronts, 32 query rows each) walks the sample's key tiles of 64 keys from the sample
-// start to the diagonal:
+// per-die queues in worklist order (longest causal cost first).  Per item the workgroup
+// (4 wavefronts, 32 query rows each) walks the sample's keys from the sample start to the diagonal.
+//
 //   S^T = K Q^T      K tile from LDS (A operand), Q fragments held in registers (B operand);
 //                    the accumulator then has one query per lane column, its keys in-lane, so
 //                    the row max/sum needs a single exchange with lane^32.
 //   P^T -> bf16      used directly as the B operand of the next product (no shuffle);
 //   O^T += V^T P^T   V tile kept in its natural [key][dim] layout in LDS and read with the
 //                    transposing LDS load, in the key order the accumulator rows have.
-// K and V tiles go global -> LDS directly (no staging registers), double buffered, with an XOR
-// swizzle of the 16-byte chunks applied on the global side.  exp is taken in base 2 with
+//
+// K and V tiles (64 keys) go global -> LDS directly (no staging registers), double buffered, with
+// an XOR swizzle of the 16-byte chunks applied on the global side.  exp is taken in base 2 with
 // scale*log2(e) folded into one multiplier.
+//
+// Software pipeline inside each wave.  Keys are processed in blocks of 32; block b goes through
+//   A(b): S^T block (MFMA)   M(b): online softmax of the block (vector ALU)   B(b): O^T += V^T P^T (MFMA)
+// and the wave executes "phases": phase b issues the MFMAs of A(b+1) and B(b-1), alternating, with
+// the vector instructions of M(b) spread a few at a time behind them.  A vector instruction
+// overlaps only MFMAs of its own wave, and only about four fit behind each MFMA, so this spreading
+// is what keeps the matrix pipe busy.  One workgroup barrier per 64-key tile: K(t) and V(t-1) are
+// last read in phase 2t, so at the barrier before phase 2t+1 the copies of K(t+2) and V(t+1) are
+// issued into the buffers they leave.
+#include <type_traits>
+
 #include "common.hpp"
 
 namespace hbp {
 
-// One key tile (64 keys = two blocks of 32) for one wavefront (32 query rows).  MASKED: the tile
-// reaches past the wave's first query row, so the causal compare is applied; interior tiles skip it.
-//
-// Each 32-key block is one online-softmax step.  The two blocks are software-pipelined inside the
-// wave so that the softmax arithmetic of a block is issued, a few instructions at a time, behind the
-// MFMAs of the neighbouring product (a vector instruction only overlaps MFMAs of its own wave, and
-// only a handful fit behind each):
-//     S(0) | S(1) + softmax(0) | PV(0) + softmax(1) | PV(1)
-// LDS operand reads run PD fragments ahead of the MFMAs that consume them.  koff / voff are byte
-// offsets from `lds` that already contain the current buffer's base.
-template <int DQK, int DV, bool MASKED>
-__device__ __forceinline__ void fwd_tile(const char* lds, const int (&koff)[DQK / 16],
-                                         const int (&voff)[2][DV / 32], const Frag (&qf)[DQK / 16],
-                                         f32x16 (&oacc)[DV / 32], float& m_run, float& l_run,
-                                         float scale_log2, int k_off, int q_in, int hh) {
-  constexpr int KRB = DQK * 2, VRB = DV * 2;
-  constexpr int NC = DQK / 16, NEB = DV / 32;
-  constexpr int PD = 4;
-  constexpr int NSL = 18;  // softmax slices per block: 0 = row max, 1..16 = elements, 17 = drain
+template <int DQK, int DV>
+struct FwdWave {
+  static constexpr int BN = 64;
+  static constexpr int KRB = DQK * 2, VRB = DV * 2;  // bytes per LDS row
+  static constexpr int K_TILE = BN * KRB, V_TILE = BN * VRB;
+  static constexpr int NC = DQK / 16;   // MFMAs of A: contraction chunks of QK^T
+  static constexpr int NEB = DV / 32;   // 32-wide blocks of the head dim of V
+  static constexpr int NB = 2 * NEB;    // MFMAs of B
+  static constexpr int TOTAL = NC + NB; // MFMAs per phase; a multiple of PD
+  static constexpr int PD = 4;          // LDS read-ahead depth of the operand ring
+  static constexpr int NSL = 17;        // exp slices: 1..16 = elements, 17 = drain
+  static constexpr int EA = NSL * 2 * NC / (2 * NC + NB);  // exp slices placed behind the A MFMAs
+  static constexpr int NMP = 5;         // pieces of the row-maximum computation
 
-  f32x16 s[2];
-  Frag pf[2][2];  // [blk][j]
-#pragma unroll
-  for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) s[blk][i] = 0.f;
+  // LDS layout: [K buf0][K buf1][V buf0][V buf1].  The offsets below are absolute LDS addresses
+  // (workgroup base and current buffer included), so a read needs no address arithmetic.
+  uint32_t koff[NC];     // this lane's K fragments
+  uint32_t voff[2][NEB]; // this lane's V^T fragments
+  Frag qf[NC];
+  Frag ring[PD];         // operand read-ahead; runs on across phase boundaries
+  f32x16 oacc[NEB];
+  f32x16 s[2];           // s[b & 1] = scores of block b
+  Frag pf[2][2];         // pf[b & 1][j] = probabilities of block b, key chunk j
+  float scale_log2;
+  int q_in, hh;
+  // Online softmax state.  m_run: reference the probabilities of the current block are taken
+  // against; l_run: this lane's part of the row sum.  m_next / alpha_next / move_next: decided by
+  // the row maximum of the following block, adopted when that block becomes the current one.
+  float m_run, l_run, m_next, alpha_next, alpha_cur, pmax;
+  bool move_next, move_cur;
+  float p_cur, p_even, psum;
 
-  auto k_load = [&](int blk) {
-    return [&, blk](int c) {
-      Frag f;
-      f.u = *(const u32x4*)(lds + 32 * blk * KRB + koff[c]);
-      return f;
-    };
-  };
-  auto s_mma = [&](int blk) {
-    return [&, blk](int c, const Frag& f) { s[blk] = mfma32(f.v, qf[c].v, s[blk]); };
-  };
-  auto v_load = [&](int blk) {  // step (j, eb), eb fastest
-    return [&, blk](int i) {
-      const int eb = i % NEB, j = i / NEB;
-      const char* base = lds + (32 * blk + 16 * j) * VRB;
-      Frag f;
-      f.h[0] = lds_read_tr16(base + voff[0][eb]);
-      f.h[1] = lds_read_tr16(base + voff[1][eb]);
-      return f;
-    };
-  };
-  auto pv_mma = [&](int blk) {
-    return [&, blk](int i, const Frag& f) { oacc[i % NEB] = mfma32(f.v, pf[blk][i / NEB].v, oacc[i % NEB]); };
-  };
-
-  // softmax of one block, cut in slices.  Elements go through two stages one slice apart (exp of
-  // element e next to the sum/pack of element e-1) so no instruction waits on its predecessor.
-  float p_cur = 0.f, p_even = 0.f, psum = 0.f, alpha_deferred = 1.f;
-  bool rescale_deferred = false;
-  auto sm_slice = [&](int blk, int sl, bool defer_o_rescale) {
-    if (sl == 0) {
-      float mx = -INFINITY;
-      // element i holds key k_off + 32 blk + 4 hh + (8 (i>>2) + (i&3)): masked iff that constant
-      // exceeds d.  d is kept opaque so the compare stays "constant vs one register" instead of
-      // sixteen precomputed per-lane thresholds held across the whole loop.
-      int d = q_in - (k_off + 32 * blk + 4 * hh);
-      if (MASKED) asm volatile("" : "+v"(d));
+  __device__ __forceinline__ Frag k_frag(int blk_in_tile, int c) const {
+    Frag f;
+    f.u = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(koff[c] + 32 * blk_in_tile * KRB);
+    return f;
+  }
+  __device__ __forceinline__ Frag v_frag(int blk_in_tile, int i) const {  // i = (j, eb), eb fastest
+    const int eb = i % NEB, j = i / NEB;
+    const uint32_t base = (32 * blk_in_tile + 16 * j) * VRB;
+    Frag f;
+    f.h[0] = lds_read_tr16_at(voff[0][eb] + base);
+    f.h[1] = lds_read_tr16_at(voff[1][eb] + base);
+    return f;
+  }
+  // first PD operands of a phase that reads K block `blk_in_tile`
+  __device__ __forceinline__ void preload_k(int blk_in_tile) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        if (MASKED) {
-          if (8 * (i >> 2) + (i & 3) > d) s[blk][i] = -INFINITY;
+    for (int i = 0; i < PD; ++i) ring[i] = k_frag(blk_in_tile, i);
+  }
+
+  // Values produced by the slices are consumed a phase later, behind a branch; without an anchor
+  // the compiler sinks their whole computation out of the MFMA shadow to just before that use.
+  template <class T>
+  static __device__ __forceinline__ void pin(T& x) {
+    asm volatile("" : "+v"(x));
+  }
+
+  // A(0) alone (pipeline prologue): s[0] = K_0 Q^T
+  __device__ __forceinline__ void first_scores() {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s[0][i] = 0.f;
+    LdsChain<NC, PD> c;
+    auto load = [&](int i) { return k_frag(0, i); };
+    c.prefill(load);
+    c.run(load, [&](int i, const Frag& f) { s[0] = mfma32(f.v, qf[i].v, s[0]); });
+  }
+
+  // Row maximum of a block (scores in s[par]) in NMP pieces, and with it the decision whether the
+  // reference moves when this block becomes the current one.  d: causal threshold of this lane,
+  // element i of the block is masked iff 8 (i>>2) + (i&3) > d (pass mask = false for blocks that
+  // lie entirely below the diagonal).
+  // Lazy rescale: the reference only moves when some row's maximum grew by more than 2^8; until
+  // then probabilities are taken relative to the old reference (they stay below 2^8, and O and l
+  // share the reference, so the result is unchanged).
+  template <bool MAYBE_MASKED>
+  __device__ __forceinline__ void max_piece(int par, int d, int piece) {
+    if (piece < 4) {
+      if (piece == 0) pmax = -INFINITY;
+#pragma unroll
+      for (int i = 4 * piece; i < 4 * piece + 4; ++i) {
+        if (MAYBE_MASKED) {
+          if (8 * (i >> 2) + (i & 3) > d) s[par][i] = -INFINITY;
         }
-        mx = fmaxf(mx, s[blk][i]);
+        pmax = fmaxf(pmax, s[par][i]);
       }
-      mx = max_with_other_half(mx) * scale_log2;  // scale > 0: max commutes with the scaling
-      // Lazy rescale: the running reference m_run only moves when some row's maximum grew by more
-      // than 2^8; until then probabilities are taken relative to the old reference (they stay
-      // below 2^8, and O and l share the reference, so the result is unchanged).
-      if (__builtin_amdgcn_ballot_w64(mx > m_run + 8.0f) != 0) {
-        const float m_new = fmaxf(m_run, mx);  // finite: key 0 of the sample is visible to every row
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-        m_run = m_new;
-        l_run *= alpha;
-        if (defer_o_rescale) {  // O is being accumulated by MFMAs in flight: scale it after them
-          alpha_deferred = alpha;
-          rescale_deferred = true;
-        } else {
-#pragma unroll
-          for (int eb = 0; eb < NEB; ++eb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) oacc[eb][i] *= alpha;
-        }
-      }
-      psum = 0.f;
+      pin(pmax);
       return;
     }
+    const float mx = max_with_other_half(pmax) * scale_log2;  // scale > 0: max commutes with the scaling
+    move_next = __builtin_amdgcn_ballot_w64(mx > m_run + 8.0f) != 0;
+    m_next = move_next ? fmaxf(m_run, mx) : m_run;  // finite: key 0 of the sample is visible to every row
+    alpha_next = __builtin_amdgcn_exp2f(m_run - m_next);
+    pin(alpha_next);
+  }
+  // causal threshold for the block that starts at in-sample key k_blk; a lane-constant.  Kept
+  // opaque so the compares stay "constant vs one register" instead of sixteen precomputed
+  // per-lane thresholds.
+  __device__ __forceinline__ int mask_threshold(int k_blk, bool masked) const {
+    int d = masked ? q_in - (k_blk + 4 * hh) : 0x7fffffff;
+    asm volatile("" : "+v"(d));
+    return d;
+  }
+  // the block whose maximum was just taken becomes the current one
+  __device__ __forceinline__ void adopt() {
+    m_run = m_next;
+    l_run *= alpha_next;
+    alpha_cur = alpha_next;
+    move_cur = move_next;
+    psum = 0.f;
+  }
+  // exp of the current block (scores in s[par]).  Elements go through two stages one slice apart
+  // (exp of element e next to the sum/pack of element e-1) so no instruction waits on the one
+  // before it.  sl = 1..NSL.
+  __device__ __forceinline__ void exp_slice(int par, int sl) {
     const float p_prev = p_cur;
     if (sl <= 16) {
-      const int e = sl - 1;
-      p_cur = __builtin_amdgcn_exp2f(__builtin_fmaf(s[blk][e], scale_log2, -m_run));
+      p_cur = __builtin_amdgcn_exp2f(__builtin_fmaf(s[par][sl - 1], scale_log2, -m_run));
+      pin(p_cur);
     }
     if (sl >= 2) {
       const int e = sl - 2;  // element whose exp was issued one slice ago
       psum += p_prev;        // unrounded: LSE must not inherit the bf16 rounding of P
-      if (e & 1) pf[blk][e >> 3].w[(e & 7) >> 1] = pack_bf16(p_even, p_prev);
-      else p_even = p_prev;
+      pin(psum);
+      if (e & 1) {
+        pf[par][e >> 3].w[(e & 7) >> 1] = pack_bf16(p_even, p_prev);
+        pin(pf[par][e >> 3].w[(e & 7) >> 1]);
+      } else {
+        p_even = p_prev;
+      }
     }
-    if (sl == NSL - 1) l_run += psum;
-  };
-
-  LdsChain<NC, PD> cs;
-  cs.prefill(k_load(0));
-  cs.run(k_load(0), s_mma(0));
-  cs.prefill(k_load(1));
-  cs.template run_with<NSL>(k_load(1), s_mma(1), [&](int sl) { sm_slice(0, sl, false); });
-  LdsChain<2 * NEB, PD> cv;
-  cv.prefill(v_load(0));
-  cv.template run_with<NSL>(v_load(0), pv_mma(0), [&](int sl) { sm_slice(1, sl, true); });
-  cv.prefill(v_load(1));
-  if (rescale_deferred) {
-#pragma unroll
-    for (int eb = 0; eb < NEB; ++eb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) oacc[eb][i] *= alpha_deferred;
+    if (sl == NSL) l_run += psum;
   }
-  cv.run(v_load(1), pv_mma(1));
-}
 
-template <int DQK, int DV>
-__global__ __launch_bounds__(kThreads, 2) void fwd_kernel(const FwdParams p) {
-  constexpr int BM = 128, BN = 64;
-  constexpr int KRB = DQK * 2, VRB = DV * 2;  // bytes per LDS row
-  constexpr int K_TILE = BN * KRB, V_TILE = BN * VRB;
-  constexpr int NC = DQK / 16;   // contraction chunks of QK^T
-  constexpr int NEB = DV / 32;   // 32-wide blocks of the head dim of V
+  // What phase b of a wave consists of.  The wave's blocks are 0..nb-1; block nb-1 is the diagonal
+  // one, the only one that needs the causal compare.
+  struct Parts {
+    bool a;     // A(b+1) and the row maximum of block b+1:  b+1 < nb
+    bool e;     // exp of block b:                             b < nb
+    bool b;     // B(b-1):                                     1 <= b <= nb
+    bool mask;  // block b+1 is the diagonal block
+  };
+  static __device__ __forceinline__ Parts parts_of(int b, int nb) {
+    return Parts{b + 1 < nb, b < nb, b >= 1 && b <= nb, b + 2 == nb};
+  }
+
+  // Phase b (PAR = b & 1).  MFMAs: A(b+1) then B(b-1), both on block 1-PAR of their tiles.  Behind
+  // them: the exp slices of block b, and behind the B MFMAs (when the scores of block b+1 are
+  // complete) the pieces of that block's row maximum.  HOT: every part present and no mask, known
+  // at compile time; otherwise `pt` says (wave-uniform) which parts run.  With part a the ring must
+  // hold the first PD K fragments on entry; an odd phase leaves the ring holding those of the
+  // following even phase (same K tile, no barrier in between).  k_next: in-sample index of the
+  // first key of block b+1.
+  template <int PAR, bool HOT, class Copy>
+  __device__ __forceinline__ void phase(int k_next, Parts pt, Copy copy) {
+    constexpr int NXT = 1 - PAR;
+    const bool do_a = HOT || pt.a, do_e = HOT || pt.e, do_b = HOT || pt.b;
+    int d = 0;
+    if (!HOT) d = mask_threshold(k_next, pt.mask);
+    if (do_e) adopt();
+    else move_cur = false;
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int j = 0; j < TOTAL; ++j) {
+      if (j < NC) {
+        if (do_a) {
+          if (j == 0) {
+            const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            s[NXT] = mfma32(ring[0].v, qf[0].v, zero);
+          } else {
+            s[NXT] = mfma32(ring[j % PD].v, qf[j].v, s[NXT]);
+          }
+        }
+      } else if (do_b) {
+        const int i = j - NC;
+        oacc[i % NEB] = mfma32(ring[j % PD].v, pf[NXT][i / NEB].v, oacc[i % NEB]);
+      }
+      const int jn = j + PD;  // operand to fetch now
+      if (jn < NC) {
+        if (do_a) ring[jn % PD] = k_frag(NXT, jn);
+      } else if (jn < TOTAL) {
+        if (do_b) ring[jn % PD] = v_frag(NXT, jn - NC);
+      } else if (PAR == 1) {
+        ring[jn % PD] = k_frag(PAR, jn - TOTAL);
+      }
+      if (do_e) {
+        const int lo = j < NC ? j * EA / NC : EA + (j - NC) * (NSL - EA) / NB;
+        const int hi = j < NC ? (j + 1) * EA / NC : EA + (j - NC + 1) * (NSL - EA) / NB;
+#pragma unroll
+        for (int sl = lo; sl < hi; ++sl) exp_slice(PAR, sl + 1);
+      }
+      if (do_a && j >= NC) {
+#pragma unroll
+        for (int piece = 0; piece < NMP; ++piece) {
+          const int slot = 2 + piece * (NB - 2) / NMP;
+          if ((slot < NB ? slot : NB - 1) == j - NC) max_piece<!HOT>(NXT, d, piece);
+        }
+      }
+      copy(j);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (move_cur) {  // blocks up to b-1 are in O: bring them to the reference block b was taken against
+#pragma unroll
+      for (int eb = 0; eb < NEB; ++eb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) oacc[eb][i] *= alpha_cur;
+    }
+  }
+  template <int PAR>
+  __device__ __forceinline__ void any_phase(int b, int nb) {
+    const Parts pt = parts_of(b, nb);
+    if (pt.a || pt.e || pt.b) phase<PAR, false>(32 * (b + 1), pt, [](int) {});
+  }
+};
+
+// HP: query heads per workgroup.  With HP = 2 the workgroup has eight wavefronts, four per head, and
+// both heads (same kv head) work off the same K/V tiles in LDS, which halves the L2 -> LDS copy
+// traffic per MFMA; it needs an even group size.  Either way a compute unit holds eight wavefronts.
+template <int DQK, int DV, int HP>
+__global__ __launch_bounds__(kThreads * HP, 2 / HP) void fwd_kernel(const FwdParams p) {
+  constexpr int NW = 4 * HP;
+  using W = FwdWave<DQK, DV>;
+  constexpr int BM = 128, BN = W::BN;
+  constexpr int KRB = W::KRB, VRB = W::VRB, K_TILE = W::K_TILE, V_TILE = W::V_TILE;
+  constexpr int NC = W::NC, NEB = W::NEB;
 
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  // [K buf0][K buf1][V buf0][V buf1]
   char* const k_lds = smem;
   char* const v_lds = smem + 2 * K_TILE;
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int rw = wave & 3;  // which 32 rows of the query tile
   const int lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
 
+  W w;
+  const uint32_t lds0 = lds_address(smem);
+  w.hh = hh;
+  w.scale_log2 = p.scale_log2;
   // per-lane LDS byte offsets of the A operands (row part that does not depend on the 32-key block)
-  int koff[NC];
 #pragma unroll
-  for (int c = 0; c < NC; ++c) koff[c] = l32 * KRB + swz<DQK>(2 * c + hh, l32) * 16;
-  int voff[2][NEB];
+  for (int c = 0; c < NC; ++c) w.koff[c] = lds0 + l32 * KRB + swz<DQK>(2 * c + hh, l32) * 16;
   {
     const int G = lane >> 4, s = lane & 15;
     const int k8 = 4 * hh + (s >> 2);
@@ -171,23 +279,24 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(const FwdParams p) {
 #pragma unroll
       for (int eb = 0; eb < NEB; ++eb) {
         const int c = 4 * eb + 2 * (G & 1) + ((s & 3) >> 1);
-        voff[r][eb] = 2 * K_TILE + (8 * r + k8) * VRB + swz<DV>(c, 8 * r + k8) * 16 + (s & 1) * 8;
+        w.voff[r][eb] = lds0 + 2 * K_TILE + (8 * r + k8) * VRB + swz<DV>(c, 8 * r + k8) * 16 + (s & 1) * 8;
       }
   }
-  TileLoader<DQK, BN> k_loader;
-  TileLoader<DV, BN> v_loader;
-  k_loader.init(wave, lane);
-  v_loader.init(wave, lane);
   const uint32_t k_stride_b = (uint32_t)p.k_st * 2, v_stride_b = (uint32_t)p.v_st * 2;
+  FullTileLoader<DQK, BN, NW> k_loader;
+  FullTileLoader<DV, BN, NW> v_loader;
+  k_loader.init(wave, lane, k_stride_b);
+  v_loader.init(wave, lane, v_stride_b);
 
   uint32_t n_done = 0;
   uint64_t t_first = 0, t_last = 0, t_busy = 0;
 
-  const WorkQueues wq{p.counter, p.n_tiles, p.Hkv, p.g};
+  const WorkQueues wq{p.counter, p.n_tiles, p.Hkv, p.g / HP};
   int q_cur = xcc_id_reg() & (kNumXcd - 1), q_tried = 0;
   for (;;) {
     int tile_idx, h;
     if (!next_item(wq, (int*)smem, tid, q_cur, q_tried, tile_idx, h)) break;
+    h = h * HP + (wave >> 2);  // this wave's head
     uint64_t t0 = 0;
     if (p.prof && tid == 0) {
       t0 = wall_clock64();
@@ -200,83 +309,154 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(const FwdParams p) {
     if (ok) {
       s0 = p.cu[tl.sample];
       s1 = p.cu[tl.sample + 1];
+      // tiles start a multiple of 32 rows into their sample: each wave then has exactly one key
+      // block that crosses its diagonal
       ok = s0 >= 0 && s1 <= p.T && s0 <= tl.row_begin && tl.row_begin < tl.row_end &&
-           tl.row_end <= s1 && tl.row_end - tl.row_begin <= BM;
+           tl.row_end <= s1 && tl.row_end - tl.row_begin <= BM && (tl.row_begin - s0) % 32 == 0;
     }
     if (ok) {
       const int r0 = tl.row_begin, r1 = tl.row_end;
       const int kh = h / p.g;
-      const int qw0 = r0 - s0 + 32 * wave;  // in-sample index of this wave's first query
-      const int my_row = r0 + 32 * wave + l32;
+      const int qw0 = r0 - s0 + 32 * rw;  // in-sample index of this wave's first query
+      const int my_row = r0 + 32 * rw + l32;
       const bool row_valid = my_row < r1;
-      const bool wave_active = r0 + 32 * wave < r1;
+      const bool wave_active = r0 + 32 * rw < r1;
+      const int nb = wave_active ? qw0 / 32 + 1 : 0;  // this wave's key blocks are 0..nb-1
 
       const int n_keys = r1 - s0;  // keys 0..n_keys-1 (in-sample) are needed by this tile
-      const int nkt = (n_keys + BN - 1) / BN;
+      const int nkt = (n_keys + BN - 1) / BN;  // nb <= 2 nkt
       const uint16_t* kbase = p.k + (int64_t)s0 * p.k_st + (int64_t)kh * p.k_sh;
       const uint16_t* vbase = p.v + (int64_t)s0 * p.v_st + (int64_t)kh * p.v_sh;
-
-      auto issue = [&](int kt) {
-        const int k_off = kt * BN;
-        const int valid = n_keys - k_off;  // >= 1
-        k_loader.issue(kbase + (int64_t)k_off * p.k_st, k_stride_b, valid, k_lds + (kt & 1) * K_TILE, wave);
-        v_loader.issue(vbase + (int64_t)k_off * p.v_st, v_stride_b, valid, v_lds + (kt & 1) * V_TILE, wave);
+      auto issue_k = [&](int t) {
+        if (t < nkt)
+          k_loader.issue(kbase + (int64_t)t * BN * p.k_st, k_stride_b, n_keys - t * BN, k_lds + (t & 1) * K_TILE, wave, lane);
       };
-      issue(0);
+      auto issue_v = [&](int t) {
+        if (t < nkt)
+          v_loader.issue(vbase + (int64_t)t * BN * p.v_st, v_stride_b, n_keys - t * BN, v_lds + (t & 1) * V_TILE, wave, lane);
+      };
+      issue_k(0);
+      issue_v(0);
+      issue_k(1);
 
       // Q fragments (B operand of S^T = K Q^T): lane holds query l32, dims 16c+8hh..+7
-      Frag qf[NC];
       {
         const uint16_t* qp = p.q + (int64_t)my_row * p.q_st + (int64_t)h * p.q_sh + 8 * hh;
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
-          if (row_valid) qf[c].u = *(const u32x4*)(qp + 16 * c);
-          else qf[c].u = u32x4{0, 0, 0, 0};
+          if (row_valid) w.qf[c].u = *(const u32x4*)(qp + 16 * c);
+          else w.qf[c].u = u32x4{0, 0, 0, 0};
         }
       }
-
-      f32x16 oacc[NEB];
 #pragma unroll
       for (int eb = 0; eb < NEB; ++eb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) oacc[eb][i] = 0.f;
-      float m_run = -INFINITY, l_run = 0.f;
-      const int q_in = qw0 + l32;
+        for (int i = 0; i < 16; ++i) w.oacc[eb][i] = 0.f;
+      w.m_run = -INFINITY;
+      w.l_run = 0.f;
+      w.q_in = qw0 + l32;
+      w.p_cur = w.p_even = w.psum = 0.f;
 
-      int cur_buf = 0;
-      auto point_offsets_at = [&](int buf) {  // move every LDS offset to the other buffer
-        const int dk = buf ? K_TILE : -K_TILE, dv = buf ? V_TILE : -V_TILE;
+      int k_buf = 0, v_buf = 0;  // buffers the LDS offsets currently point at
+      auto point_k = [&](int buf) {
+        if (buf != k_buf) {
+          const int d = buf ? K_TILE : -K_TILE;
 #pragma unroll
-        for (int c = 0; c < NC; ++c) koff[c] += dk;
-#pragma unroll
-        for (int r = 0; r < 2; ++r)
-#pragma unroll
-          for (int eb = 0; eb < NEB; ++eb) voff[r][eb] += dv;
-        cur_buf = buf;
+          for (int c = 0; c < NC; ++c) w.koff[c] += d;
+          k_buf = buf;
+        }
       };
-      auto begin_tile = [&](int kt) {
+      auto point_v = [&](int buf) {
+        if (buf != v_buf) {
+          const int d = buf ? V_TILE : -V_TILE;
+#pragma unroll
+          for (int r = 0; r < 2; ++r)
+#pragma unroll
+            for (int eb = 0; eb < NEB; ++eb) w.voff[r][eb] += d;
+          v_buf = buf;
+        }
+      };
+      auto tile_sync = [&](int t) {  // between phases 2t and 2t+1
+#ifndef HBP_NOWAIT
         wait_async_loads();
-        __syncthreads();  // tile kt has landed for every wave; tile kt-1 is no longer read
-        if (kt + 1 < nkt) issue(kt + 1);
-        if ((kt & 1) != cur_buf) point_offsets_at(kt & 1);
+#endif
+        __syncthreads();  // K(t+1) and V(t) have landed; K(t) and V(t-1) are no longer read
+        point_k((t + 1) & 1);
+        point_v(t & 1);
       };
-      // Interior tiles (entirely below this wave's first query row) and diagonal tiles run in two
-      // separate loops, one code variant each; every wave still passes nkt barriers in total.
-      const int n_interior = wave_active ? min(nkt, (qw0 + 1) / BN) : 0;
-      int kt = 0;
-      for (; kt < n_interior; ++kt) {
-        begin_tile(kt);
-        fwd_tile<DQK, DV, false>(smem, koff, voff, qf, oacc, m_run, l_run, p.scale_log2, kt * BN, q_in, hh);
+      auto tile_barrier = [&](int t) {  // the same, with the next copies issued in one go
+        tile_sync(t);
+#ifndef HBP_NODMA
+        issue_k(t + 2);
+        issue_v(t + 1);
+#endif
+      };
+
+      wait_async_loads();
+      __syncthreads();  // K(0), V(0), K(1) have landed
+      if (nb > 0) {
+        w.first_scores();
+        w.preload_k(1);
+        const int d0 = w.mask_threshold(0, nb == 1);
+#pragma unroll
+        for (int piece = 0; piece < W::NMP; ++piece) w.template max_piece<true>(0, d0, piece);
+        w.move_next = false;  // O is still zero: nothing to rescale
       }
-      for (; kt < nkt; ++kt) {
-        begin_tile(kt);
-        if (wave_active && kt * BN <= qw0 + 31)  // else: nothing at or below the diagonal
-          fwd_tile<DQK, DV, true>(smem, koff, voff, qf, oacc, m_run, l_run, p.scale_log2, kt * BN, q_in, hh);
+
+      // Tiles whose two phases both run every part unmasked (phases 1 .. nb-3) get a loop of
+      // their own with one code variant; every wave passes nkt barriers in total.
+      const int t_hot_end = nb >= 6 ? (nb - 4) / 2 + 1 : 1;  // hot tiles are 1 .. t_hot_end-1
+      int t = 0;
+      if (nkt > 0) {
+        w.template any_phase<0>(0, nb);
+        tile_barrier(0);
+        w.preload_k(0);
+        w.template any_phase<1>(1, nb);
+        t = 1;
       }
-      if (cur_buf) point_offsets_at(0);
+      for (; t < t_hot_end; ++t) {
+        w.template phase<0, true>(64 * t + 32, typename W::Parts{}, [](int) {});
+        tile_sync(t);
+        w.preload_k(0);
+        // the copies of K(t+2) and V(t+1) go out one at a time behind this phase's MFMAs (a burst
+        // of them would hold the wave for as long as the address path takes to drain)
+        const uint16_t* kg = kbase + (int64_t)(t + 2) * BN * p.k_st;
+        const uint16_t* vg = vbase + (int64_t)(t + 1) * BN * p.v_st;
+        const int k_valid = n_keys - (t + 2) * BN, v_valid = n_keys - (t + 1) * BN;
+        const char* k_dst = k_lds + (t & 1) * K_TILE;
+        const char* v_dst = v_lds + ((t + 1) & 1) * V_TILE;
+        constexpr int NKC = decltype(k_loader)::PER_WAVE, NVC = decltype(v_loader)::PER_WAVE;
+        constexpr int GAP = W::TOTAL / (NKC + NVC) > 0 ? W::TOTAL / (NKC + NVC) : 1;
+        w.template phase<1, true>(64 * t + 64, typename W::Parts{}, [&](int j) {
+#pragma unroll
+          for (int c = 0; c < NKC + NVC; ++c) {
+            const int slot = c * GAP < W::TOTAL ? c * GAP : W::TOTAL - 1;
+            if (slot != j) continue;
+#ifdef HBP_NODMA
+            continue;
+#endif
+            if (c < NKC) {
+              if (k_valid > 0) k_loader.issue_one(c, kg, k_stride_b, k_valid, k_dst, wave, lane);
+            } else {
+              v_loader.issue_one(c - NKC, vg, v_stride_b, v_valid, v_dst, wave, lane);
+            }
+          }
+        });
+      }
+      for (; t < nkt; ++t) {
+        w.template any_phase<0>(2 * t, nb);
+        tile_barrier(t);
+        w.preload_k(0);
+        w.template any_phase<1>(2 * t + 1, nb);
+      }
+      // B of the last block when the wave's blocks fill every tile: V(nkt-1) is still in LDS and
+      // the offsets already point at it
+      if (nb == 2 * nkt) w.template any_phase<0>(nb, nb);
+      point_k(0);
+      point_v(0);
 
       // finalise: O = acc / l, LSE = (m + log2 l) * ln 2
-      const float l_tot = l_run + xor32(l_run);
+      const float l_tot = w.l_run + xor32(w.l_run);
       if (row_valid) {
         const float inv = 1.f / l_tot;
         uint16_t* op = p.o + (int64_t)my_row * p.o_st + (int64_t)h * p.o_sh + 4 * hh;
@@ -284,12 +464,12 @@ __global__ __launch_bounds__(kThreads, 2) void fwd_kernel(const FwdParams p) {
         for (int eb = 0; eb < NEB; ++eb)
 #pragma unroll
           for (int b = 0; b < 4; ++b) {
-            u32x2 w = {pack_bf16(oacc[eb][4 * b] * inv, oacc[eb][4 * b + 1] * inv),
-                       pack_bf16(oacc[eb][4 * b + 2] * inv, oacc[eb][4 * b + 3] * inv)};
-            *(u32x2*)(op + 32 * eb + 8 * b) = w;
+            u32x2 wv = {pack_bf16(w.oacc[eb][4 * b] * inv, w.oacc[eb][4 * b + 1] * inv),
+                        pack_bf16(w.oacc[eb][4 * b + 2] * inv, w.oacc[eb][4 * b + 3] * inv)};
+            *(u32x2*)(op + 32 * eb + 8 * b) = wv;
           }
         if (hh == 0)
-          p.lse[(int64_t)h * p.T + my_row] = (m_run + log2f(l_tot)) * 0.6931471805599453f;
+          p.lse[(int64_t)h * p.T + my_row] = (w.m_run + log2f(l_tot)) * 0.6931471805599453f;
       }
     }
     if (p.prof && tid == 0) {
@@ -321,27 +501,33 @@ int launch_zero_counters(int32_t* counters, hipStream_t s) {
   return (int)hipGetLastError();
 }
 
-template <int DQK, int DV>
-static int launch_fwd_t(const FwdParams& p, int grid, hipStream_t s) {
+template <int DQK, int DV, int HP>
+static int launch_fwd_hp(const FwdParams& p, int n_cu, hipStream_t s) {
   constexpr int lds_bytes = 2 * 64 * (DQK * 2 + DV * 2);
   static bool attr_set = false;
   if (!attr_set) {
-    const hipError_t e = hipFuncSetAttribute((const void*)fwd_kernel<DQK, DV>,
+    const hipError_t e = hipFuncSetAttribute((const void*)fwd_kernel<DQK, DV, HP>,
                                              hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (e != hipSuccess) return (int)e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((fwd_kernel<DQK, DV>), dim3(grid), dim3(kThreads), lds_bytes, s, p);
+  const int64_t n_items = (int64_t)p.n_tiles * (p.Hq / HP), cap = (int64_t)n_cu * (2 / HP);
+  const int grid = (int)(n_items < cap ? n_items : cap);
+  hipLaunchKernelGGL((fwd_kernel<DQK, DV, HP>), dim3(grid), dim3(kThreads * HP), lds_bytes, s, p);
   return (int)hipGetLastError();
 }
+template <int DQK, int DV>
+static int launch_fwd_t(const FwdParams& p, int n_cu, hipStream_t s) {
+  return p.g % 2 == 0 ? launch_fwd_hp<DQK, DV, 2>(p, n_cu, s) : launch_fwd_hp<DQK, DV, 1>(p, n_cu, s);
+}
 
-int launch_fwd(int d_qk, int d_v, const FwdParams& p, int grid, hipStream_t s, hipEvent_t ev0,
+int launch_fwd(int d_qk, int d_v, const FwdParams& p, int n_cu, hipStream_t s, hipEvent_t ev0,
                hipEvent_t ev1) {
   if (ev0 && hipEventRecord(ev0, s) != hipSuccess) return (int)hipErrorInvalidValue;
   int e;
-  if (d_qk == 64 && d_v == 64) e = launch_fwd_t<64, 64>(p, grid, s);
-  else if (d_qk == 128 && d_v == 128) e = launch_fwd_t<128, 128>(p, grid, s);
-  else if (d_qk == 192 && d_v == 128) e = launch_fwd_t<192, 128>(p, grid, s);
+  if (d_qk == 64 && d_v == 64) e = launch_fwd_t<64, 64>(p, n_cu, s);
+  else if (d_qk == 128 && d_v == 128) e = launch_fwd_t<128, 128>(p, n_cu, s);
+  else if (d_qk == 192 && d_v == 128) e = launch_fwd_t<192, 128>(p, n_cu, s);
   else return (int)hipErrorInvalidValue;
   if (e == 0 && ev1 && hipEventRecord(ev1, s) != hipSuccess) return (int)hipErrorInvalidValue;
   return e;
