@@ -57,7 +57,9 @@ __device__ __forceinline__ void prof_write(const ProfAcc& a, hbp_profile_rec* pr
 
 // ------------------------------------------------------------------------------------- dQ
 template <int DQK, int DV>
-__global__ __launch_bounds__(kThreads, 1) void bwd_dq_kernel(const BwdParams p) {
+// Two workgroups per compute unit where the kernel fits 256 registers (d_qk <= 128): the second
+// wavefront on each SIMD fills the issue slots the first one leaves open.
+__global__ __launch_bounds__(kThreads, DQK <= 128 ? 2 : 1) void bwd_dq_kernel(const BwdParams p) {
   constexpr int BM = 128, BN = 64;
   constexpr int KRB = DQK * 2, VRB = DV * 2;
   constexpr int K_TILE = BN * KRB, V_TILE = BN * VRB;
@@ -75,12 +77,14 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dq_kernel(const BwdParams p) 
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
 
-  // LDS byte offsets from smem; they contain the current buffer's base (toggled once per tile)
-  int koff[NC], vnoff[NCV], ktoff[2][NDB];
+  // Absolute LDS addresses of this lane's fragments: workgroup base and current buffer included
+  // (toggled once per tile), so a read needs no address arithmetic.
+  const uint32_t lds0 = lds_address(smem);
+  uint32_t koff[NC], vnoff[NCV], ktoff[2][NDB];
 #pragma unroll
-  for (int c = 0; c < NC; ++c) koff[c] = l32 * KRB + swz<DQK>(2 * c + hh, l32) * 16;
+  for (int c = 0; c < NC; ++c) koff[c] = lds0 + l32 * KRB + swz<DQK>(2 * c + hh, l32) * 16;
 #pragma unroll
-  for (int c = 0; c < NCV; ++c) vnoff[c] = 2 * K_TILE + l32 * VRB + swz<DV>(2 * c + hh, l32) * 16;
+  for (int c = 0; c < NCV; ++c) vnoff[c] = lds0 + 2 * K_TILE + l32 * VRB + swz<DV>(2 * c + hh, l32) * 16;
   {
     const int G = lane >> 4, s = lane & 15;
     const int k8 = 4 * hh + (s >> 2);
@@ -89,7 +93,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dq_kernel(const BwdParams p) 
 #pragma unroll
       for (int db = 0; db < NDB; ++db) {
         const int c = 4 * db + 2 * (G & 1) + ((s & 3) >> 1);
-        ktoff[r][db] = (8 * r + k8) * KRB + swz<DQK>(c, 8 * r + k8) * 16 + (s & 1) * 8;
+        ktoff[r][db] = lds0 + (8 * r + k8) * KRB + swz<DQK>(c, 8 * r + k8) * 16 + (s & 1) * 8;
       }
   }
 
@@ -167,8 +171,8 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dq_kernel(const BwdParams p) 
       auto sd_load = [&](int blk) {
         return [&, blk](int i) {
           Frag a;
-          if (i < NC) a.u = *(const u32x4*)(smem + 32 * blk * KRB + koff[i]);
-          else a.u = *(const u32x4*)(smem + 32 * blk * VRB + vnoff[i - NC]);
+          if (i < NC) a.u = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(koff[i] + 32 * blk * KRB);
+          else a.u = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(vnoff[i - NC] + 32 * blk * VRB);
           return a;
         };
       };
@@ -195,10 +199,10 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dq_kernel(const BwdParams p) 
         };
       };
       auto gr_frag = [&](int blk, int j, int db) {
-        const char* base = smem + (32 * blk + 16 * j) * KRB;
+        const uint32_t base = (32 * blk + 16 * j) * KRB;
         Frag a;
-        a.h[0] = lds_read_tr16(base + ktoff[0][db]);
-        a.h[1] = lds_read_tr16(base + ktoff[1][db]);
+        a.h[0] = lds_read_tr16_at(ktoff[0][db] + base);
+        a.h[1] = lds_read_tr16_at(ktoff[1][db] + base);
         return a;
       };
       // slices 0..16 of a block: slice k issues exp for element k (k < 16) and finishes element
@@ -340,11 +344,14 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
 
-  int qoff[NC], dooff[NCV], qtoff[2][NDB], dotoff[2][NEB];
+  // Absolute LDS addresses of this lane's fragments: workgroup base and current buffer included
+  // (toggled once per step), so a read needs no address arithmetic.
+  const uint32_t lds0 = lds_address(smem);
+  uint32_t qoff[NC], dooff[NCV], qtoff[2][NDB], dotoff[2][NEB];
 #pragma unroll
-  for (int c = 0; c < NC; ++c) qoff[c] = l32 * QRB + swz<DQK>(2 * c + hh, l32) * 16;
+  for (int c = 0; c < NC; ++c) qoff[c] = lds0 + l32 * QRB + swz<DQK>(2 * c + hh, l32) * 16;
 #pragma unroll
-  for (int c = 0; c < NCV; ++c) dooff[c] = 2 * Q_TILE + l32 * ORB + swz<DV>(2 * c + hh, l32) * 16;
+  for (int c = 0; c < NCV; ++c) dooff[c] = lds0 + 2 * Q_TILE + l32 * ORB + swz<DV>(2 * c + hh, l32) * 16;
   {
     const int G = lane >> 4, s = lane & 15;
     const int k8 = 4 * hh + (s >> 2);
@@ -353,18 +360,18 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
 #pragma unroll
       for (int db = 0; db < NDB; ++db) {
         const int c = 4 * db + 2 * (G & 1) + ((s & 3) >> 1);
-        qtoff[r][db] = (8 * r + k8) * QRB + swz<DQK>(c, 8 * r + k8) * 16 + (s & 1) * 8;
+        qtoff[r][db] = lds0 + (8 * r + k8) * QRB + swz<DQK>(c, 8 * r + k8) * 16 + (s & 1) * 8;
       }
 #pragma unroll
       for (int eb = 0; eb < NEB; ++eb) {
         const int c = 4 * eb + 2 * (G & 1) + ((s & 3) >> 1);
-        dotoff[r][eb] = 2 * Q_TILE + (8 * r + k8) * ORB + swz<DV>(c, 8 * r + k8) * 16 + (s & 1) * 8;
+        dotoff[r][eb] = lds0 + 2 * Q_TILE + (8 * r + k8) * ORB + swz<DV>(c, 8 * r + k8) * 16 + (s & 1) * 8;
       }
     }
   }
-  // byte offsets (from smem) of this lane's LSE2 / D rows inside the current buffer
-  int lseoff = 2 * Q_TILE + 2 * O_TILE + 16 * hh;
-  int dvoff = lseoff + 2 * BQ * 4;
+  // LDS addresses of this lane's LSE2 / D rows inside the current buffer
+  uint32_t lseoff = lds0 + 2 * Q_TILE + 2 * O_TILE + 16 * hh;
+  uint32_t dvoff = lseoff + 2 * BQ * 4;
 
   TileLoader<DQK, BQ> q_loader;
   TileLoader<DV, BQ> o_loader;
@@ -460,8 +467,8 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
         auto sd_load = [&](int sub) {
           return [&, sub](int i) {
             Frag a;
-            if (i < NC) a.u = *(const u32x4*)(smem + 32 * sub * QRB + qoff[i]);
-            else a.u = *(const u32x4*)(smem + 32 * sub * ORB + dooff[i - NC]);
+            if (i < NC) a.u = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(qoff[i] + 32 * sub * QRB);
+            else a.u = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(dooff[i - NC] + 32 * sub * ORB);
             return a;
           };
         };
@@ -496,14 +503,14 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
             Frag a;
             if (i < 2 * NEB) {
               const int eb = i % NEB, j = i / NEB;
-              const char* base = smem + (32 * sub + 16 * j) * ORB;
-              a.h[0] = lds_read_tr16(base + dotoff[0][eb]);
-              a.h[1] = lds_read_tr16(base + dotoff[1][eb]);
+              const uint32_t base = (32 * sub + 16 * j) * ORB;
+              a.h[0] = lds_read_tr16_at(dotoff[0][eb] + base);
+              a.h[1] = lds_read_tr16_at(dotoff[1][eb] + base);
             } else {
               const int db = (i - 2 * NEB) % NDB, j = (i - 2 * NEB) / NDB;
-              const char* base = smem + (32 * sub + 16 * j) * QRB;
-              a.h[0] = lds_read_tr16(base + qtoff[0][db]);
-              a.h[1] = lds_read_tr16(base + qtoff[1][db]);
+              const uint32_t base = (32 * sub + 16 * j) * QRB;
+              a.h[0] = lds_read_tr16_at(qtoff[0][db] + base);
+              a.h[1] = lds_read_tr16_at(qtoff[1][db] + base);
             }
             return a;
           };
@@ -523,8 +530,8 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
         float e_cur = 0.f, d_prev = 0.f;      // exp of element i (stage 1), D of the element in stage 2
         float pr_even = 0.f, ds_even = 0.f;
         auto rows_prefetch = [&](int sub, int b) {
-          l4n = *(const f32x4*)(smem + (32 * sub + 8 * b) * 4 + lseoff);
-          d4n = *(const f32x4*)(smem + (32 * sub + 8 * b) * 4 + dvoff);
+          l4n = *(const __attribute__((address_space(3))) f32x4*)(uintptr_t)(lseoff + (32 * sub + 8 * b) * 4);
+          d4n = *(const __attribute__((address_space(3))) f32x4*)(uintptr_t)(dvoff + (32 * sub + 8 * b) * 4);
         };
         auto stage2 = [&](Sub& x, int sub, int i, float e_val, float d_val, auto masked) {
           const int b = i >> 2, v = i & 3;

@@ -212,6 +212,7 @@ struct FullTileLoader {
   __device__ __forceinline__ void issue_clamped(int ii, const uint16_t* g, uint32_t stride_bytes, int rows_valid,
                                                 const char* lds_tile, int wave, int lane) const {
     if (!has(ii, wave)) return;
+    asm volatile("" : "+v"(lane));  // recomputed here each time: not worth registers held across the main loops
     const int pos = (wave + NW * ii) * 1024 + lane * 16;
     const int row = pos / RB, cpos = (pos % RB) / 16;
     const int last = rows_valid - 1;

@@ -101,7 +101,7 @@ struct FwdWave {
   // reference moves when this block becomes the current one.  d: causal threshold of this lane,
   // element i of the block is masked iff 8 (i>>2) + (i&3) > d (pass mask = false for blocks that
   // lie entirely below the diagonal).
-  // Lazy rescale: the reference only moves when some row's maximum grew by more than 2^8; until
+  // Lazy rescale: a row's reference only moves when its maximum grew by more than 2^8; until
   // then probabilities are taken relative to the old reference (they stay below 2^8, and O and l
   // share the reference, so the result is unchanged).
   template <bool MAYBE_MASKED>
@@ -119,9 +119,12 @@ struct FwdWave {
       return;
     }
     const float mx = max_with_other_half(pmax) * scale_log2;  // scale > 0: max commutes with the scaling
-    move_next = __builtin_amdgcn_ballot_w64(mx > m_run + 8.0f) != 0;
-    m_next = move_next ? fmaxf(m_run, mx) : m_run;  // finite: key 0 of the sample is visible to every row
+    // decided row by row (both lanes of a row see the same mx), so the choice is a plain vector
+    // select; the wave-wide "did any row move" is only needed a phase later, for O
+    const bool grew = mx > m_run + 8.0f;
+    m_next = grew ? fmaxf(m_run, mx) : m_run;  // finite: key 0 of the sample is visible to every row
     alpha_next = __builtin_amdgcn_exp2f(m_run - m_next);
+    move_next = __builtin_amdgcn_ballot_w64(grew) != 0;
     pin(alpha_next);
   }
   // causal threshold for the block that starts at in-sample key k_blk; a lane-constant.  Kept
@@ -377,19 +380,15 @@ __global__ __launch_bounds__(kThreads * HP, 2 / HP) void fwd_kernel(const FwdPar
         }
       };
       auto tile_sync = [&](int t) {  // between phases 2t and 2t+1
-#ifndef HBP_NOWAIT
         wait_async_loads();
-#endif
         __syncthreads();  // K(t+1) and V(t) have landed; K(t) and V(t-1) are no longer read
         point_k((t + 1) & 1);
         point_v(t & 1);
       };
       auto tile_barrier = [&](int t) {  // the same, with the next copies issued in one go
         tile_sync(t);
-#ifndef HBP_NODMA
         issue_k(t + 2);
         issue_v(t + 1);
-#endif
       };
 
       wait_async_loads();
@@ -432,9 +431,6 @@ __global__ __launch_bounds__(kThreads * HP, 2 / HP) void fwd_kernel(const FwdPar
           for (int c = 0; c < NKC + NVC; ++c) {
             const int slot = c * GAP < W::TOTAL ? c * GAP : W::TOTAL - 1;
             if (slot != j) continue;
-#ifdef HBP_NODMA
-            continue;
-#endif
             if (c < NKC) {
               if (k_valid > 0) k_loader.issue_one(c, kg, k_stride_b, k_valid, k_dst, wave, lane);
             } else {
