@@ -56,9 +56,9 @@ __device__ __forceinline__ void prof_write(const ProfAcc& a, hbp_profile_rec* pr
 }
 
 // ------------------------------------------------------------------------------------- dQ
-template <int DQK, int DV>
 // Two workgroups per compute unit where the kernel fits 256 registers (d_qk <= 128): the second
 // wavefront on each SIMD fills the issue slots the first one leaves open.
+template <int DQK, int DV>
 __global__ __launch_bounds__(kThreads, DQK <= 128 ? 2 : 1) void bwd_dq_kernel(const BwdParams p) {
   constexpr int BM = 128, BN = 64;
   constexpr int KRB = DQK * 2, VRB = DV * 2;
