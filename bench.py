@@ -23,6 +23,11 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA (published)
 
+# HBM bytes of one launch of the dominant kernel (backward key-tile kernel) on workload 3, from the two
+# rocprofv3 counter runs summarised in profiles/hbm_traffic_mixed32k.md:
+# FETCH_SIZE 5 455 790 KiB x 2.0 (calibration factor) + WRITE_SIZE 131 530 KiB x 1.0.
+DKDV_TRAFFIC_BYTES = {3: int((5455790 * 2.0 + 131530 * 1.0) * 1024)}
+
 
 class HipEvents:
     """hipEvent_t handles through the HIP runtime (timing on the stream the kernels run on)."""
@@ -224,7 +229,8 @@ def main():
         "roofline": {"kernel": "bwd_dkdv_kernel (key-tile persistent kernel; S, dP, dV, dK products)",
                      "bound": "mfma", "flop_per_launch": dkdv_flops,
                      "achieved": bwd_tf, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": bwd_tf / PEAK_BF16_TFLOPS, "traffic": None},
+                     "frac": bwd_tf / PEAK_BF16_TFLOPS,
+                     "traffic": DKDV_TRAFFIC_BYTES.get(args.config) if args.seed == 0 else None},
         "busy_time_spread": {"fwd": spread_f, "bwd_dkdv": spread_b, "bwd_dq": spread_q},
     }
     if not args.no_cpu_baseline:
