@@ -373,11 +373,11 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
   uint32_t lseoff = lds0 + 2 * Q_TILE + 2 * O_TILE + 16 * hh;
   uint32_t dvoff = lseoff + 2 * BQ * 4;
 
-  TileLoader<DQK, BQ> q_loader;
-  TileLoader<DV, BQ> o_loader;
-  q_loader.init(wave, lane);
-  o_loader.init(wave, lane);
   const uint32_t q_stride_b = (uint32_t)p.q_st * 2, o_stride_b = (uint32_t)p.o_st * 2;
+  FullTileLoader<DQK, BQ> q_loader;
+  FullTileLoader<DV, BQ> o_loader;
+  q_loader.init(wave, lane, q_stride_b);
+  o_loader.init(wave, lane, o_stride_b);
 
   ProfAcc pa;
   const WorkQueues wq{p.counter, p.n_tiles, p.Hkv, 1};
@@ -415,9 +415,9 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
         const int valid = s_len - qb;  // >= 1
         const int buf = step & 1;
         q_loader.issue(p.q + (int64_t)(s0 + qb) * p.q_st + (int64_t)hq * p.q_sh, q_stride_b, valid,
-                       q_lds + buf * Q_TILE, wave);
+                       q_lds + buf * Q_TILE, wave, lane);
         o_loader.issue(p.d_o + (int64_t)(s0 + qb) * p.o_st + (int64_t)hq * p.o_sh, o_stride_b, valid,
-                       o_lds + buf * O_TILE, wave);
+                       o_lds + buf * O_TILE, wave, lane);
         if (wave < 2) {
           // issued through the same untracked path as the tiles: the compiler must not see an LDS
           // write here, or it would drain every outstanding copy before the next LDS read
