@@ -194,6 +194,18 @@ def main():
     spread_b = busy_spread(pa.profile_records(H.HBP_BWD))
     spread_q = busy_spread(pa.profile_records(H.HBP_BWD_DQ))
 
+    # second roofline denominator: what the matrix pipes of this part sustain on MFMA-only code
+    # (every SIMD busy, ~4 ms, same process right after the timed steps, so under the same power state)
+    sink = torch.empty(256 * 512, dtype=torch.float32, device="cuda")
+    p0, p1 = ev.create(), ev.create()
+    n_probe = 120000
+    H.hbp_mfma_probe(256, 20000, sink, stream)   # warm
+    ev.record(p0, stream)
+    H.hbp_mfma_probe(256, n_probe, sink, stream)
+    ev.record(p1, stream)
+    torch.cuda.synchronize()
+    sustained_tf = 256 * 8 * n_probe * 32768 / (ev.elapsed_ms(p0, p1) * 1e-3) / 1e12
+
     if args.calib_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
@@ -220,7 +232,10 @@ def main():
                    "n_kv_heads": w.n_kv_heads, "d_qk": w.d_qk, "d_v": w.d_v, "causal_pairs": pairs,
                    "pack_cost_sum_s2": pa.pack_cost, "useful_tflop_fwd": fwd_flops / 1e12,
                    "useful_tflop_bwd": bwd_flops / 1e12},
+        "useful_tflops_4gemm_bwd": (fwd_flops + dkdv_flops) / (ms_per_step * 1e-3) / 1e12,
         "kernels": {"fwd_ms_avg": float(fwd_k.mean()), "fwd_ms_min": float(fwd_k.min()),
+                    "fwd_ms_median": float(np.median(fwd_k)), "bwd_dkdv_ms_median": float(np.median(bwd_k)),
+                    "bwd_dq_ms_median": float(np.median(dq_k)),
                     "fwd_tflops": fwd_tf, "bwd_dkdv_ms_avg": float(bwd_k.mean()),
                     "bwd_dkdv_ms_min": float(bwd_k.min()), "bwd_dkdv_tflops": bwd_tf,
                     "bwd_dq_ms_avg": float(dq_k.mean()), "bwd_dq_ms_min": float(dq_k.min()),
@@ -230,6 +245,7 @@ def main():
                      "bound": "mfma", "flop_per_launch": dkdv_flops,
                      "achieved": bwd_tf, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": bwd_tf / PEAK_BF16_TFLOPS,
+                     "sustained_mfma_only_tflops": sustained_tf, "frac_of_sustained": bwd_tf / sustained_tf,
                      "traffic": DKDV_TRAFFIC_BYTES.get(args.config) if args.seed == 0 else None},
         "busy_time_spread": {"fwd": spread_f, "bwd_dkdv": spread_b, "bwd_dq": spread_q},
     }

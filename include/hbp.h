@@ -180,6 +180,19 @@ hbp_status hbp_varlen_attn_bwd(const hbp_attn_desc* desc, const void* q, const v
  */
 hbp_status hbp_set_kernel_events(int32_t which, void* start_event, void* stop_event);
 
+/*
+ * hbp_mfma_probe — measurement aid: the second denominator of the roofline.  Launches, on `stream`,
+ * one kernel in which every SIMD of `n_cu` compute units (two wavefronts each) issues nothing but
+ * independent 32x32x16 bf16 MFMAs on register-resident data: `mfma_per_wave` of them per wavefront
+ * (rounded down to a multiple of 4).  The caller times the launch (events on the same stream);
+ * executed flops = n_cu * 8 * mfma_per_wave * 32768.  That rate is what the matrix pipes of this
+ * part sustain under its power limit, i.e. the practical ceiling next to the published peak.
+ * `sink` (device, >= n_cu * 512 floats) receives one value per thread so the work is not removed;
+ * it carries no information.  Returns HBP_ERR_INVALID_ARG for NULL sink, n_cu < 1 or
+ * mfma_per_wave < 4, HBP_ERR_DEVICE if the launch fails.  Asynchronous; allocates nothing.
+ */
+hbp_status hbp_mfma_probe(int32_t n_cu, int32_t mfma_per_wave, float* sink, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

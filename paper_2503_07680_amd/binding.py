@@ -16,7 +16,7 @@ HBP_TILES_QUERY, HBP_TILES_KEY = 0, 1
 
 EXPORTED_SYMBOLS = ["hbp_status_string", "hbp_pack_plan", "hbp_tile_rows", "hbp_workspace_bytes",
                     "hbp_profile_capacity", "hbp_varlen_attn_fwd", "hbp_varlen_attn_bwd",
-                    "hbp_set_kernel_events"]
+                    "hbp_set_kernel_events", "hbp_mfma_probe"]
 
 # numpy view of hbp_profile_rec
 PROFILE_DTYPE = np.dtype([("hw_id", "<u4"), ("xcc_id", "<u4"), ("n_items", "<u4"), ("reserved", "<u4"),
@@ -77,6 +77,8 @@ def load_library():
                                         ctypes.c_size_t, vp, vp, vp]
     lib.hbp_set_kernel_events.restype = i32
     lib.hbp_set_kernel_events.argtypes = [i32, vp, vp]
+    lib.hbp_mfma_probe.restype = i32
+    lib.hbp_mfma_probe.argtypes = [i32, i32, vp, vp]
     _lib = lib
     return lib
 
@@ -170,6 +172,13 @@ def hbp_varlen_attn_bwd(desc: AttnDesc, q, k, v, o, lse, d_o, cu_seqlens, q_tile
         stream)
     if st != 0:
         raise HbpError(st, "hbp_varlen_attn_bwd")
+
+
+def hbp_mfma_probe(n_cu: int, mfma_per_wave: int, sink, stream=None) -> None:
+    """Launch the MFMA-only probe kernel (n_cu workgroups of 8 waves); the caller times it."""
+    st = load_library().hbp_mfma_probe(int(n_cu), int(mfma_per_wave), _ptr(sink), _ptr(stream))
+    if st != 0:
+        raise HbpError(st, "hbp_mfma_probe")
 
 
 def hbp_set_kernel_events(which: int, start_event: Optional[int], stop_event: Optional[int]) -> None:

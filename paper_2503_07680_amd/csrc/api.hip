@@ -90,6 +90,35 @@ extern "C" const char* hbp_status_string(hbp_status s) {
   }
 }
 
+namespace {
+// nothing but independent MFMAs: four accumulators per wave, operands in registers
+__global__ __launch_bounds__(512) void mfma_probe_kernel(float* sink, int n_groups) {
+  hbp::bf16x8 a, b;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    a[i] = (__bf16)(threadIdx.x * 0.001f + i);
+    b[i] = (__bf16)(0.5f + blockIdx.x * 0.01f);
+  }
+  hbp::f32x16 c[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) c[j][i] = 0.f;
+  for (int it = 0; it < n_groups; ++it) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) c[j] = hbp::mfma32(a, b, c[j]);
+  }
+  sink[blockIdx.x * blockDim.x + threadIdx.x] = c[0][3] + c[1][3] + c[2][3] + c[3][3];
+}
+}  // namespace
+
+extern "C" hbp_status hbp_mfma_probe(int32_t n_cu, int32_t mfma_per_wave, float* sink, void* stream) {
+  if (!sink || n_cu < 1 || mfma_per_wave < 4) return HBP_ERR_INVALID_ARG;
+  hipLaunchKernelGGL(mfma_probe_kernel, dim3(n_cu), dim3(512), 0, static_cast<hipStream_t>(stream), sink,
+                     mfma_per_wave / 4);
+  return hipGetLastError() == hipSuccess ? HBP_OK : HBP_ERR_DEVICE;
+}
+
 extern "C" hbp_status hbp_set_kernel_events(int32_t which, void* start_event, void* stop_event) {
   if (which != HBP_FWD && which != HBP_BWD && which != HBP_BWD_DQ) return HBP_ERR_INVALID_ARG;
   if ((start_event == nullptr) != (stop_event == nullptr)) return HBP_ERR_INVALID_ARG;
