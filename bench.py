@@ -80,7 +80,7 @@ def busy_spread(rec: np.ndarray):
             "workgroups": int(used.sum())}
 
 
-def cpu_baseline(w, cu, target_pairs=2.0e7):
+def cpu_baseline(w, cu, target_pairs=2.0e8):
     """Time the fp64 oracle (fwd + dQ + dK/dV) on a bounded sub-pack of the same workload."""
     import hbp_workloads as wl
     import oracle
