@@ -116,6 +116,22 @@ def cpu_baseline(w, cu, target_pairs=2.0e8):
                       % (what, int(sum(sub_lens)), pairs, len(q_heads), len(kv_heads))}
 
 
+def planner_timing(n=1_000_000):
+    """Host side: the multi-level Balance Packing planner over a synthetic dataset of n lengths
+    (lognormal(600, 1.2) clipped to [16, 131072], four packing groups); the paper quotes about 5 s per
+    million samples for its whole-dataset packing (Appendix, packing time), on other hardware."""
+    import paper_2503_07680_amd as H
+    r = np.random.default_rng(0)
+    lengths = np.clip(np.rint(np.exp(r.normal(np.log(600.0), 1.2, n))), 16, 131072).astype(np.int32)
+    groups, per_batch, sp = [4096, 16384, 32768, 131072], [32, 8, 4, 1], [1, 2, 4, 8]
+    H.hbp_balance_packing(lengths[:1000], groups, per_batch, sp, 0)
+    t0 = time.perf_counter()
+    batches, packs, items, m = H.hbp_balance_packing(lengths, groups, per_batch, sp, 0)
+    dt = time.perf_counter() - t0
+    return {"samples": n, "seconds": dt, "samples_per_s": n / dt, "n_packs": int(len(packs)),
+            "n_batches": int(len(batches)), "metrics": m, "packing_groups": groups}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -249,6 +265,7 @@ def main():
                      "traffic": DKDV_TRAFFIC_BYTES.get(args.config) if args.seed == 0 else None},
         "busy_time_spread": {"fwd": spread_f, "bwd_dkdv": spread_b, "bwd_dq": spread_q},
     }
+    out["balance_packing"] = planner_timing()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, pa.cu)
     print(json.dumps(out))

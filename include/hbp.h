@@ -180,6 +180,67 @@ hbp_status hbp_varlen_attn_bwd(const hbp_attn_desc* desc, const void* q, const v
  */
 hbp_status hbp_set_kernel_events(int32_t which, void* start_event, void* stop_event);
 
+/* ---- multi-level Balance Packing planner (host only) ------------------------------------------ */
+
+/* one pack: `n_items` sample indices starting at pack_items[first_item] */
+typedef struct {
+  int32_t level;      /* packing group i (0-based): the pack is filled to at most group_lens[level] */
+  int32_t first_item;
+  int32_t n_items;
+  int32_t n_tokens;   /* sum of the lengths of its samples */
+  int64_t attn_cost;  /* attention complexity a = sum len^2 (paper Section 3.1; Attention Balance Sort) */
+} hbp_pack;
+
+/* one mini-batch: `n_packs` packs of one level starting at packs[first_pack] (one pack per device) */
+typedef struct {
+  int32_t level, first_pack, n_packs, reserved;
+} hbp_batch;
+
+/* Section 3.1 metrics of a plan (see hbp_balance_packing for how they are evaluated) */
+typedef struct {
+  double dbr, pr, abr, cr, ave_t;
+} hbp_pack_metrics;
+
+/*
+ * hbp_balance_packing — the paper's Balance Packing (Section 4.2, Algorithm 2) over a whole dataset
+ * of sample lengths.  Host only, integer, deterministic.
+ *
+ *   GroupData (appendix):  sample x joins group D_i when len(x) is in (l_{i-1}, l_i], l_0 = 0,
+ *                          l_i = group_lens[i] (strictly increasing).
+ *   for i = n_levels-1 .. 0:
+ *     Packing(D_i, l_i):   first-fit decreasing (the paper allows any packer): samples by length
+ *                          descending, ties in input order, each into the first pack (creation
+ *                          order) it fits.
+ *     GreedyFill (appendix): for every pack, for j = i-1 .. 0, for every x still in D_j in input
+ *                          order: if tokens(pack) + len(x) <= l_i the sample moves into the pack.
+ *     Balance Batching:    attention complexity a = sum len^2 per pack, packs sorted by a
+ *                          descending (ties: creation order), cut into runs of packs_per_batch[i]
+ *                          packs; a short last run is kept.
+ *   Shuffle of all batches: Fisher-Yates from the end with j = r mod (k+1), r from the splitmix64
+ *                          stream of shuffle_seed.
+ *
+ * Outputs, in final order (batches as shuffled, inside a batch the packs in sorted order):
+ * batches[n_batches], packs[n_packs], pack_items[n_samples] (every sample index exactly once).
+ * Pass pack_items = packs = batches = NULL for a size query (counts and metrics only); otherwise all
+ * three must be non-NULL with item_cap >= n_samples, pack_cap / batch_cap >= the counts
+ * (HBP_ERR_CAPACITY if not; the counts are still reported).
+ * metrics_or_null: one pack is one device's input of an iteration.  DBR and ABR: the equations'
+ * sum(v_max - v_i) / (v_max N) over the packs of a batch (v = tokens, resp. a), averaged over the
+ * batches of full size; PR = padding / capacity = sum(l_i - tokens) / sum l_i over all packs;
+ * CR = tokens in packs of levels with level_sp[i] > 1 over all tokens (level_sp NULL: 0);
+ * Ave-T = tokens per pack.
+ * Errors: HBP_ERR_INVALID_ARG for NULL counts, n_levels < 1, group_lens not strictly increasing and
+ * positive, packs_per_batch[i] < 1, level_sp[i] < 1, a length <= 0 or > the largest group length.
+ * All pointers are host memory owned by the caller.
+ */
+hbp_status hbp_balance_packing(const int32_t* lengths, int32_t n_samples,
+                               const int32_t* group_lens, const int32_t* packs_per_batch,
+                               const int32_t* level_sp, int32_t n_levels, uint64_t shuffle_seed,
+                               int32_t* pack_items, int32_t item_cap,
+                               hbp_pack* packs, int32_t pack_cap, int32_t* n_packs_out,
+                               hbp_batch* batches, int32_t batch_cap, int32_t* n_batches_out,
+                               hbp_pack_metrics* metrics_or_null);
+
 /*
  * hbp_mfma_probe — measurement aid: the second denominator of the roofline.  Launches, on `stream`,
  * one kernel in which every SIMD of `n_cu` compute units (two wavefronts each) issues nothing but

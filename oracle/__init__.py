@@ -7,6 +7,7 @@ imports the product package.
 from .attention import (attn_fwd, attn_bwd_dq, attn_bwd_dkdv, prob_row, build_oracle,
                         oracle_threads)
 from .plan import pack_plan, pack_cost, balance_ratio
+from . import balance_packing
 
 __all__ = ["attn_fwd", "attn_bwd_dq", "attn_bwd_dkdv", "prob_row", "build_oracle",
-           "oracle_threads", "pack_plan", "pack_cost", "balance_ratio"]
+           "oracle_threads", "pack_plan", "pack_cost", "balance_ratio", "balance_packing"]

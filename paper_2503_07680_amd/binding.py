@@ -16,7 +16,18 @@ HBP_TILES_QUERY, HBP_TILES_KEY = 0, 1
 
 EXPORTED_SYMBOLS = ["hbp_status_string", "hbp_pack_plan", "hbp_tile_rows", "hbp_workspace_bytes",
                     "hbp_profile_capacity", "hbp_varlen_attn_fwd", "hbp_varlen_attn_bwd",
-                    "hbp_set_kernel_events", "hbp_mfma_probe"]
+                    "hbp_set_kernel_events", "hbp_mfma_probe", "hbp_balance_packing"]
+
+# numpy views of hbp_pack / hbp_batch
+PACK_DTYPE = np.dtype([("level", "<i4"), ("first_item", "<i4"), ("n_items", "<i4"), ("n_tokens", "<i4"),
+                       ("attn_cost", "<i8")])
+BATCH_DTYPE = np.dtype([("level", "<i4"), ("first_pack", "<i4"), ("n_packs", "<i4"), ("reserved", "<i4")])
+
+
+class PackMetrics(ctypes.Structure):
+    """Mirror of ``hbp_pack_metrics``."""
+    _fields_ = [("dbr", ctypes.c_double), ("pr", ctypes.c_double), ("abr", ctypes.c_double),
+                ("cr", ctypes.c_double), ("ave_t", ctypes.c_double)]
 
 # numpy view of hbp_profile_rec
 PROFILE_DTYPE = np.dtype([("hw_id", "<u4"), ("xcc_id", "<u4"), ("n_items", "<u4"), ("reserved", "<u4"),
@@ -77,6 +88,9 @@ def load_library():
                                         ctypes.c_size_t, vp, vp, vp]
     lib.hbp_set_kernel_events.restype = i32
     lib.hbp_set_kernel_events.argtypes = [i32, vp, vp]
+    lib.hbp_balance_packing.restype = i32
+    lib.hbp_balance_packing.argtypes = [vp, i32, vp, vp, vp, i32, ctypes.c_uint64, vp, i32, vp, i32, vp,
+                                        vp, i32, vp, vp]
     lib.hbp_mfma_probe.restype = i32
     lib.hbp_mfma_probe.argtypes = [i32, i32, vp, vp]
     _lib = lib
@@ -124,6 +138,39 @@ def hbp_pack_plan(lengths: Sequence[int], pack_len: int, tile_rows: int, kind: i
     if st != 0:
         raise HbpError(st, "hbp_pack_plan")
     return cu, int(nc.value), tiles, cost, int(pc.value)
+
+
+def hbp_balance_packing(lengths: Sequence[int], group_lens: Sequence[int], packs_per_batch: Sequence[int],
+                        level_sp: Optional[Sequence[int]] = None, shuffle_seed: int = 0, lists: bool = True):
+    """The multi-level Balance Packing planner.  Returns (batches BATCH_DTYPE[nb], packs PACK_DTYPE[np],
+    pack_items int32[n_samples], metrics dict); with lists=False only the counts and metrics:
+    (n_batches, n_packs, None, metrics).  Host only."""
+    lib = load_library()
+    L = np.ascontiguousarray(lengths, dtype=np.int32)
+    G = np.ascontiguousarray(group_lens, dtype=np.int32)
+    B = np.ascontiguousarray(packs_per_batch, dtype=np.int32)
+    S = None if level_sp is None else np.ascontiguousarray(level_sp, dtype=np.int32)
+    if B.size != G.size or (S is not None and S.size != G.size):
+        raise HbpError(1, "hbp_balance_packing")
+    n_p, n_b = ctypes.c_int32(), ctypes.c_int32()
+    m = PackMetrics()
+    ptr = lambda a: a.ctypes.data if a is not None and a.size else None
+    args = (ptr(L), int(L.size), ptr(G), ptr(B), ptr(S), int(G.size), int(shuffle_seed) & (2 ** 64 - 1))
+    st = lib.hbp_balance_packing(*args, None, 0, None, 0, ctypes.byref(n_p), None, 0, ctypes.byref(n_b),
+                                 ctypes.byref(m))
+    if st != 0:
+        raise HbpError(st, "hbp_balance_packing")
+    metrics = {"DBR": m.dbr, "PR": m.pr, "ABR": m.abr, "CR": m.cr, "AveT": m.ave_t}
+    if not lists:
+        return int(n_b.value), int(n_p.value), None, metrics
+    items = np.zeros(max(int(L.size), 1), dtype=np.int32)
+    packs = np.zeros(max(n_p.value, 1), dtype=PACK_DTYPE)
+    batches = np.zeros(max(n_b.value, 1), dtype=BATCH_DTYPE)
+    st = lib.hbp_balance_packing(*args, items.ctypes.data, int(L.size), packs.ctypes.data, n_p.value,
+                                 ctypes.byref(n_p), batches.ctypes.data, n_b.value, ctypes.byref(n_b), None)
+    if st != 0:
+        raise HbpError(st, "hbp_balance_packing")
+    return batches[:n_b.value], packs[:n_p.value], items[:L.size], metrics
 
 
 def hbp_tile_rows(d_qk: int, d_v: int, which: int) -> int:
