@@ -8,6 +8,7 @@ from .attention import (attn_fwd, attn_bwd_dq, attn_bwd_dkdv, prob_row, build_or
                         oracle_threads)
 from .plan import pack_plan, pack_cost, balance_ratio
 from . import balance_packing
+from . import loss
 
 __all__ = ["attn_fwd", "attn_bwd_dq", "attn_bwd_dkdv", "prob_row", "build_oracle",
-           "oracle_threads", "pack_plan", "pack_cost", "balance_ratio", "balance_packing"]
+           "oracle_threads", "pack_plan", "pack_cost", "balance_ratio", "balance_packing", "loss"]
