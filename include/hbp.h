@@ -50,7 +50,7 @@ typedef struct {
 } hbp_tile;
 
 enum { HBP_TILES_QUERY = 0, HBP_TILES_KEY = 1 };
-enum { HBP_FWD = 0, HBP_BWD = 1, HBP_BWD_DQ = 2 }; /* forward; backward (its dK/dV kernel); backward's dQ kernel */
+enum { HBP_FWD = 0, HBP_BWD = 1, HBP_BWD_DQ = 2, HBP_LOSS = 3 }; /* forward; backward (its dK/dV kernel); backward's dQ kernel; the cross-entropy kernel */
 
 /*
  * hbp_pack_plan — host only, integer only, deterministic.
@@ -171,7 +171,7 @@ hbp_status hbp_varlen_attn_bwd(const hbp_attn_desc* desc, const void* q, const v
 
 /*
  * hbp_set_kernel_events — measurement hook.  When both events are non-NULL, every later call of
- * the entry point that launches the chosen kernel (which = HBP_FWD, HBP_BWD, HBP_BWD_DQ) records
+ * the entry point that launches the chosen kernel (which = HBP_FWD, HBP_BWD, HBP_BWD_DQ, HBP_LOSS) records
  * `start` on its stream immediately before, and `stop` immediately after, that persistent kernel
  * (the forward kernel; the dK/dV kernel; the dQ kernel), so a caller can time that one launch with
  * hipEventElapsedTime.  Events are hipEvent_t passed as void*, owned by the caller; pass NULLs to
@@ -240,6 +240,42 @@ hbp_status hbp_balance_packing(const int32_t* lengths, int32_t n_samples,
                                hbp_pack* packs, int32_t pack_cap, int32_t* n_packs_out,
                                hbp_batch* batches, int32_t batch_cap, int32_t* n_batches_out,
                                hbp_pack_metrics* metrics_or_null);
+
+/* ---- packed cross-entropy with the paper's loss normalisers ------------------------------------ */
+
+enum { HBP_LOSS_TOKEN_MEAN = 0, HBP_LOSS_SAMPLE_MEAN = 1, HBP_LOSS_STABLE = 2 };
+
+/* bytes of device workspace hbp_packed_ce needs (256-byte aligned base) */
+hbp_status hbp_packed_ce_workspace_bytes(int32_t total_tokens, int32_t n_samples, size_t* bytes_out);
+
+/*
+ * hbp_packed_ce — token cross-entropy over a packed buffer, reduced with one of the normalisers of
+ * the paper's Section 4.3 (normaliser equation), and its gradient, in one pass over the logits.
+ *
+ *   CE_r      = logsumexp(logits[r,:]) - logits[r, labels[r]]          for labels[r] >= 0
+ *   loss      = sum_r w_r CE_r
+ *   dlogits   = w_r (softmax(logits[r,:]) - onehot(labels[r]))         (zero rows where labels[r] < 0)
+ *   w_r       = 1 / sum_i T_i                (HBP_LOSS_TOKEN_MEAN;  T_i = loss tokens of sample i)
+ *               1 / (T_i n_samples)          (HBP_LOSS_SAMPLE_MEAN; i = the row's sample)
+ *               1 / (n_samples t_ave)        (HBP_LOSS_STABLE; t_ave = the GLOBAL mean of T_i, which the
+ *                                             caller reduces over its data-parallel ranks)
+ * A batch element of the paper's equation is one sample of the pack (rows cu_seqlens[i] ..
+ * cu_seqlens[i+1]), B_l = n_samples.  A sample without loss tokens contributes nothing.
+ *
+ * All pointers are DEVICE memory owned by the caller: logits bf16 [T, V] with row stride
+ * `logit_stride_t` elements (0 = V); labels int32 [T] (negative or >= V: no loss on that token);
+ * cu_seqlens int32 [n_samples + 1] with cu_seqlens[0] = 0, cu_seqlens[n_samples] = T;
+ * dlogits_or_null bf16 [T, V] dense; loss_out one float; token_loss_or_null float [T] (CE_r, 0 where
+ * no label).  V and the stride must be multiples of 8 and the logits 16-byte aligned
+ * (HBP_ERR_UNSUPPORTED otherwise).  Rows up to 131072 entries are read once; longer rows twice.
+ * The loss is summed in a fixed order (bit-stable).  Asynchronous on `stream`; allocates nothing.
+ * Errors: HBP_ERR_INVALID_ARG (NULL pointers, negative sizes, bad normaliser, t_ave <= 0 for
+ * HBP_LOSS_STABLE), HBP_ERR_WORKSPACE, HBP_ERR_DEVICE.  total_tokens = 0 writes loss 0.
+ */
+hbp_status hbp_packed_ce(const void* logits, int64_t logit_stride_t, int32_t total_tokens, int32_t vocab,
+                         const int32_t* labels, const int32_t* cu_seqlens, int32_t n_samples,
+                         int32_t normalizer, float t_ave, void* dlogits_or_null, float* loss_out,
+                         float* token_loss_or_null, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * hbp_mfma_probe — measurement aid: the second denominator of the roofline.  Launches, on `stream`,

@@ -16,7 +16,8 @@ HBP_TILES_QUERY, HBP_TILES_KEY = 0, 1
 
 EXPORTED_SYMBOLS = ["hbp_status_string", "hbp_pack_plan", "hbp_tile_rows", "hbp_workspace_bytes",
                     "hbp_profile_capacity", "hbp_varlen_attn_fwd", "hbp_varlen_attn_bwd",
-                    "hbp_set_kernel_events", "hbp_mfma_probe", "hbp_balance_packing"]
+                    "hbp_set_kernel_events", "hbp_mfma_probe", "hbp_balance_packing",
+                    "hbp_packed_ce_workspace_bytes", "hbp_packed_ce"]
 
 # numpy views of hbp_pack / hbp_batch
 PACK_DTYPE = np.dtype([("level", "<i4"), ("first_item", "<i4"), ("n_items", "<i4"), ("n_tokens", "<i4"),
@@ -91,6 +92,11 @@ def load_library():
     lib.hbp_balance_packing.restype = i32
     lib.hbp_balance_packing.argtypes = [vp, i32, vp, vp, vp, i32, ctypes.c_uint64, vp, i32, vp, i32, vp,
                                         vp, i32, vp, vp]
+    lib.hbp_packed_ce_workspace_bytes.restype = i32
+    lib.hbp_packed_ce_workspace_bytes.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_size_t)]
+    lib.hbp_packed_ce.restype = i32
+    lib.hbp_packed_ce.argtypes = [vp, ctypes.c_int64, i32, i32, vp, vp, i32, i32, ctypes.c_float, vp, vp, vp,
+                                  vp, ctypes.c_size_t, vp]
     lib.hbp_mfma_probe.restype = i32
     lib.hbp_mfma_probe.argtypes = [i32, i32, vp, vp]
     _lib = lib
@@ -219,6 +225,31 @@ def hbp_varlen_attn_bwd(desc: AttnDesc, q, k, v, o, lse, d_o, cu_seqlens, q_tile
         stream)
     if st != 0:
         raise HbpError(st, "hbp_varlen_attn_bwd")
+
+
+HBP_LOSS_TOKEN_MEAN, HBP_LOSS_SAMPLE_MEAN, HBP_LOSS_STABLE = 0, 1, 2
+HBP_LOSS = 3
+
+
+def hbp_packed_ce_workspace_bytes(total_tokens: int, n_samples: int) -> int:
+    out = ctypes.c_size_t()
+    st = load_library().hbp_packed_ce_workspace_bytes(int(total_tokens), int(n_samples), ctypes.byref(out))
+    if st != 0:
+        raise HbpError(st, "hbp_packed_ce_workspace_bytes")
+    return int(out.value)
+
+
+def hbp_packed_ce(logits, logit_stride_t: int, total_tokens: int, vocab: int, labels, cu_seqlens,
+                  n_samples: int, normalizer: int, t_ave: float, dlogits, loss_out, token_loss, workspace,
+                  stream=None) -> None:
+    """Device pointers (torch tensors or ints); see include/hbp.h."""
+    st = load_library().hbp_packed_ce(_ptr(logits), int(logit_stride_t), int(total_tokens), int(vocab),
+                                      _ptr(labels), _ptr(cu_seqlens), int(n_samples), int(normalizer),
+                                      float(t_ave), _ptr(dlogits), _ptr(loss_out), _ptr(token_loss),
+                                      _ptr(workspace), _nbytes(workspace) if workspace is not None else 0,
+                                      _ptr(stream))
+    if st != 0:
+        raise HbpError(st, "hbp_packed_ce")
 
 
 def hbp_mfma_probe(n_cu: int, mfma_per_wave: int, sink, stream=None) -> None:

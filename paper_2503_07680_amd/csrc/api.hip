@@ -68,7 +68,7 @@ float resolve_scale(const hbp_attn_desc* d) {
   return d->softmax_scale > 0.f ? d->softmax_scale : 1.0f / std::sqrt((float)d->d_qk);
 }
 
-hipEvent_t g_events[3][2] = {{nullptr, nullptr}, {nullptr, nullptr}, {nullptr, nullptr}};
+hipEvent_t g_events[4][2] = {{nullptr, nullptr}, {nullptr, nullptr}, {nullptr, nullptr}, {nullptr, nullptr}};
 
 int grid_for(int64_t n_items, int blocks_per_cu) {
   const int64_t cap = (int64_t)kNumCU * blocks_per_cu;
@@ -88,6 +88,66 @@ extern "C" const char* hbp_status_string(hbp_status s) {
     case HBP_ERR_DEVICE: return "HIP runtime error at launch";
     default: return "unknown status";
   }
+}
+
+namespace {
+struct CeLayout {
+  size_t weighted_off, token_loss_off, counts_off, weights_off, total;
+};
+CeLayout ce_layout(int32_t T, int32_t n) {
+  CeLayout l;
+  l.weighted_off = 0;
+  l.token_loss_off = align_up((size_t)T * sizeof(float), 256);
+  l.counts_off = l.token_loss_off + align_up((size_t)T * sizeof(float), 256);
+  l.weights_off = l.counts_off + align_up((size_t)n * sizeof(int32_t), 256);
+  l.total = l.weights_off + align_up((size_t)n * sizeof(float), 256) + 256;
+  return l;
+}
+}  // namespace
+
+extern "C" hbp_status hbp_packed_ce_workspace_bytes(int32_t total_tokens, int32_t n_samples, size_t* bytes_out) {
+  if (!bytes_out || total_tokens < 0 || n_samples < 0) return HBP_ERR_INVALID_ARG;
+  *bytes_out = ce_layout(total_tokens, n_samples).total;
+  return HBP_OK;
+}
+
+extern "C" hbp_status hbp_packed_ce(const void* logits, int64_t logit_stride_t, int32_t total_tokens,
+                                    int32_t vocab, const int32_t* labels, const int32_t* cu_seqlens,
+                                    int32_t n_samples, int32_t normalizer, float t_ave, void* dlogits_or_null,
+                                    float* loss_out, float* token_loss_or_null, void* workspace,
+                                    size_t workspace_bytes, void* stream) {
+  if (total_tokens < 0 || n_samples < 0 || vocab < 1 || !loss_out) return HBP_ERR_INVALID_ARG;
+  if (normalizer != HBP_LOSS_TOKEN_MEAN && normalizer != HBP_LOSS_SAMPLE_MEAN && normalizer != HBP_LOSS_STABLE)
+    return HBP_ERR_INVALID_ARG;
+  if (normalizer == HBP_LOSS_STABLE && !(t_ave > 0.f)) return HBP_ERR_INVALID_ARG;
+  if (total_tokens > 0 && (!logits || !labels || !cu_seqlens || n_samples < 1)) return HBP_ERR_INVALID_ARG;
+  const int64_t stride = logit_stride_t ? logit_stride_t : vocab;
+  if (stride < vocab) return HBP_ERR_SHAPE;
+  if (vocab % 8 || stride % 8 || !aligned16(logits) || !aligned16(dlogits_or_null)) return HBP_ERR_UNSUPPORTED;
+  const CeLayout lay = ce_layout(total_tokens, n_samples);
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < lay.total)
+    return HBP_ERR_WORKSPACE;
+  char* ws = static_cast<char*>(workspace);
+  hbp::CeParams p;
+  p.logits = static_cast<const uint16_t*>(logits);
+  p.stride_t = stride;
+  p.T = total_tokens;
+  p.V = vocab;
+  p.n_samples = n_samples;
+  p.normalizer = normalizer;
+  p.labels = labels;
+  p.cu = cu_seqlens;
+  p.t_ave = t_ave;
+  p.dlogits = static_cast<uint16_t*>(dlogits_or_null);
+  p.weighted = reinterpret_cast<float*>(ws + lay.weighted_off);
+  p.token_loss = token_loss_or_null ? token_loss_or_null : reinterpret_cast<float*>(ws + lay.token_loss_off);
+  p.counts = reinterpret_cast<int32_t*>(ws + lay.counts_off);
+  p.weights = reinterpret_cast<float*>(ws + lay.weights_off);
+  p.loss_out = loss_out;
+  if (hbp::launch_packed_ce(p, kNumCU, static_cast<hipStream_t>(stream), g_events[HBP_LOSS][0],
+                            g_events[HBP_LOSS][1]) != 0)
+    return HBP_ERR_DEVICE;
+  return HBP_OK;
 }
 
 namespace {
@@ -120,7 +180,7 @@ extern "C" hbp_status hbp_mfma_probe(int32_t n_cu, int32_t mfma_per_wave, float*
 }
 
 extern "C" hbp_status hbp_set_kernel_events(int32_t which, void* start_event, void* stop_event) {
-  if (which != HBP_FWD && which != HBP_BWD && which != HBP_BWD_DQ) return HBP_ERR_INVALID_ARG;
+  if (which != HBP_FWD && which != HBP_BWD && which != HBP_BWD_DQ && which != HBP_LOSS) return HBP_ERR_INVALID_ARG;
   if ((start_event == nullptr) != (stop_event == nullptr)) return HBP_ERR_INVALID_ARG;
   g_events[which][0] = static_cast<hipEvent_t>(start_event);
   g_events[which][1] = static_cast<hipEvent_t>(stop_event);

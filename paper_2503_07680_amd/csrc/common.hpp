@@ -390,6 +390,21 @@ struct BwdParams {
   hbp_profile_rec *prof, *prof_dq;
 };
 
+struct CeParams {  // packed cross-entropy
+  const uint16_t* logits;
+  int64_t stride_t;  // elements
+  int32_t T, V, n_samples, normalizer;
+  const int32_t* labels;
+  const int32_t* cu;
+  float t_ave;
+  uint16_t* dlogits;   // may be null
+  float* token_loss;   // [T]
+  float* weighted;     // [T] workspace: w_r CE_r
+  int32_t* counts;     // [n_samples] workspace: loss tokens per sample
+  float* weights;      // [n_samples] workspace
+  float* loss_out;
+};
+
 // launchers implemented in the .hip files; return hipError_t as int
 // ev0/ev1: optional events recorded around the persistent main kernel
 // n_cu: compute units to fill (the kernel picks its own workgroup shape and grid)
@@ -397,5 +412,6 @@ int launch_fwd(int d_qk, int d_v, const FwdParams& p, int n_cu, hipStream_t s, h
 // ev: {dkdv start, dkdv stop, dq start, dq stop}, entries may be null
 int launch_bwd(int d_qk, int d_v, const BwdParams& p, int grid_dq, int grid_dkdv, hipStream_t s, hipEvent_t* ev);
 int launch_zero_counters(int32_t* counters, hipStream_t s);  // the kNumXcd forward counters
+int launch_packed_ce(const CeParams& p, int n_cu, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
 
 }  // namespace hbp
