@@ -87,103 +87,126 @@ __device__ __forceinline__ int sample_of_row(const int32_t* cu, int n_samples, i
 }
 
 // NCH: 16-byte loads per thread that cover a row when HOLD (row kept in registers); with !HOLD the
-// row is streamed in kCeChunk pieces, twice.
+// row is streamed in kCeChunk pieces, twice.  In the HOLD form the registers of a chunk are refilled
+// with the same chunk of the workgroup's NEXT row as soon as its gradient is stored, so the reads of
+// one row are in flight behind the arithmetic and the stores of the row before it.
 template <int NCH, bool HOLD>
 __global__ __launch_bounds__(kCeThreads) void ce_main_kernel(const CeParams p) {
   __shared__ float slots[kCeThreads / 64];
   const int tid = threadIdx.x;
   const u32x4 kNegInf = {0xFF80FF80u, 0xFF80FF80u, 0xFF80FF80u, 0xFF80FF80u};  // bf16 -inf pairs
-  for (int r = blockIdx.x; r < p.T; r += gridDim.x) {
-    const int label = p.labels[r];
+  u32x4 held[HOLD ? NCH : 1];
+  auto has_loss = [&](int label) { return label >= 0 && label < p.V; };  // an out-of-range label: no loss
+  auto load_chunk = [&](const uint16_t* row, int c) {
+    const int e = c * kCeChunk + tid * 8;
+    return e < p.V ? __builtin_nontemporal_load((const u32x4*)(row + e)) : kNegInf;
+  };
+  int r = blockIdx.x;
+  int label = r < p.T ? p.labels[r] : -1;
+  if (HOLD && r < p.T && has_loss(label)) {
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) held[c] = load_chunk(p.logits + (int64_t)r * p.stride_t, c);
+  }
+  for (; r < p.T;) {
+    const int r_next = r + gridDim.x;
+    const int label_next = r_next < p.T ? p.labels[r_next] : -1;
+    const bool fetch_next = HOLD && r_next < p.T && has_loss(label_next);
+    const bool live = has_loss(label);  // a row without a loss: zero loss, zero gradient, no arithmetic
     const uint16_t* row = p.logits + (int64_t)r * p.stride_t;
+    const uint16_t* row_next = p.logits + (int64_t)r_next * p.stride_t;
     uint16_t* grow = p.dlogits ? p.dlogits + (int64_t)r * p.V : nullptr;
-    if (label < 0 || label >= p.V) {  // no loss on this token (an out-of-range label is treated the same)
-      if (grow) {
-        for (int e = tid * 8; e < p.V; e += kCeChunk) *(u32x4*)(grow + e) = u32x4{0, 0, 0, 0};
-      }
-      if (tid == 0) {
-        p.token_loss[r] = 0.f;
-        p.weighted[r] = 0.f;
-      }
-      continue;
-    }
     const int n_chunks = HOLD ? NCH : (p.V + kCeChunk - 1) / kCeChunk;
-    u32x4 held[HOLD ? NCH : 1];
-    // pass 1: maximum
-    float mx = -INFINITY;
-    auto chunk_max = [&](const u32x4& v) {
+    float lse2 = 0.f, w = 0.f;
+    if (live) {
+      // maximum
+      float mx = -INFINITY;
+      auto chunk_max = [&](const u32x4& v) {
 #pragma unroll
-      for (int k = 0; k < 4; ++k) mx = fmaxf(mx, fmaxf(bf16_lo(v[k]), bf16_hi(v[k])));
-    };
-    if (HOLD) {
-#pragma unroll
-      for (int c = 0; c < NCH; ++c) {
-        const int e = c * kCeChunk + tid * 8;
-        held[c] = e < p.V ? *(const u32x4*)(row + e) : kNegInf;
-      }
-#pragma unroll
-      for (int c = 0; c < NCH; ++c) chunk_max(held[c]);
-    } else {
-      for (int c = 0; c < n_chunks; ++c) {
-        const int e = c * kCeChunk + tid * 8;
-        if (e < p.V) chunk_max(*(const u32x4*)(row + e));
-      }
-    }
-    mx = block_reduce<true>(mx, slots, tid);
-    const float m2 = mx * kLog2eF;
-    // sum of exponentials, base 2 with log2(e) folded into the multiplier
-    float s = 0.f;
-    auto chunk_sum = [&](const u32x4& v) {
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        s += __builtin_amdgcn_exp2f(__builtin_fmaf(bf16_lo(v[k]), kLog2eF, -m2));
-        s += __builtin_amdgcn_exp2f(__builtin_fmaf(bf16_hi(v[k]), kLog2eF, -m2));
-      }
-    };
-    if (HOLD) {
-#pragma unroll
-      for (int c = 0; c < NCH; ++c) chunk_sum(held[c]);
-    } else {
-      for (int c = 0; c < n_chunks; ++c) {
-        const int e = c * kCeChunk + tid * 8;
-        if (e < p.V) chunk_sum(*(const u32x4*)(row + e));
-      }
-    }
-    s = block_reduce<false>(s, slots, tid);
-    const float lse2 = m2 + __builtin_amdgcn_logf(s);  // log2-sum-exp2 of the row
-    const float z_label = __uint_as_float((uint32_t)row[label] << 16);
-    const float ce = lse2 * kLn2F - z_label;
-    const float w = p.weights[sample_of_row(p.cu, p.n_samples, r)];
-    if (tid == 0) {
-      p.token_loss[r] = ce;
-      p.weighted[r] = w * ce;
-    }
-    if (grow) {
-      auto chunk_grad = [&](const u32x4& v, int e) {
-        u32x4 g;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          float a = w * __builtin_amdgcn_exp2f(__builtin_fmaf(bf16_lo(v[k]), kLog2eF, -lse2));
-          float b = w * __builtin_amdgcn_exp2f(__builtin_fmaf(bf16_hi(v[k]), kLog2eF, -lse2));
-          if (e + 2 * k == label) a -= w;
-          if (e + 2 * k + 1 == label) b -= w;
-          g[k] = pack_bf16(a, b);
-        }
-        *(u32x4*)(grow + e) = g;
+        for (int k = 0; k < 4; ++k) mx = fmaxf(mx, fmaxf(bf16_lo(v[k]), bf16_hi(v[k])));
       };
       if (HOLD) {
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
-          const int e = c * kCeChunk + tid * 8;
-          if (e < p.V) chunk_grad(held[c], e);
+          chunk_max(held[c]);
+          __builtin_amdgcn_sched_barrier(0);  // one chunk at a time: bounds the temporaries
         }
       } else {
         for (int c = 0; c < n_chunks; ++c) {
           const int e = c * kCeChunk + tid * 8;
-          if (e < p.V) chunk_grad(*(const u32x4*)(row + e), e);
+          if (e < p.V) chunk_max(*(const u32x4*)(row + e));
+        }
+      }
+      mx = block_reduce<true>(mx, slots, tid);
+      const float m2 = mx * kLog2eF;
+      // sum of exponentials, base 2 with log2(e) folded into the multiplier
+      float s = 0.f;
+      auto chunk_sum = [&](const u32x4& v) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          s += __builtin_amdgcn_exp2f(__builtin_fmaf(bf16_lo(v[k]), kLog2eF, -m2));
+          s += __builtin_amdgcn_exp2f(__builtin_fmaf(bf16_hi(v[k]), kLog2eF, -m2));
+        }
+      };
+      if (HOLD) {
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+          chunk_sum(held[c]);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      } else {
+        for (int c = 0; c < n_chunks; ++c) {
+          const int e = c * kCeChunk + tid * 8;
+          if (e < p.V) chunk_sum(*(const u32x4*)(row + e));
+        }
+      }
+      s = block_reduce<false>(s, slots, tid);
+      lse2 = m2 + __builtin_amdgcn_logf(s);  // log2-sum-exp2 of the row
+      const float z_label = __uint_as_float((uint32_t)row[label] << 16);
+      const float ce = lse2 * kLn2F - z_label;
+      w = p.weights[sample_of_row(p.cu, p.n_samples, r)];
+      if (tid == 0) {
+        p.token_loss[r] = ce;
+        p.weighted[r] = w * ce;
+      }
+    } else if (tid == 0) {
+      p.token_loss[r] = 0.f;
+      p.weighted[r] = 0.f;
+    }
+    auto chunk_grad = [&](const u32x4& v, int e) {
+      u32x4 g;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        float a = w * __builtin_amdgcn_exp2f(__builtin_fmaf(bf16_lo(v[k]), kLog2eF, -lse2));
+        float b = w * __builtin_amdgcn_exp2f(__builtin_fmaf(bf16_hi(v[k]), kLog2eF, -lse2));
+        if (e + 2 * k == label) a -= w;
+        if (e + 2 * k + 1 == label) b -= w;
+        g[k] = pack_bf16(a, b);
+      }
+      __builtin_nontemporal_store(g, (u32x4*)(grow + e));
+    };
+    if (HOLD) {
+      // the only place (after the first row) where the held registers are written
+#pragma unroll
+      for (int c = 0; c < NCH; ++c) {
+        const int e = c * kCeChunk + tid * 8;
+        if (grow && e < p.V) {
+          if (live) chunk_grad(held[c], e);
+          else __builtin_nontemporal_store(u32x4{0, 0, 0, 0}, (u32x4*)(grow + e));
+        }
+        if (fetch_next) held[c] = load_chunk(row_next, c);
+        __builtin_amdgcn_sched_barrier(0);  // keep the refill behind the store: hoisted loads would need a second set of registers
+      }
+    } else if (grow) {
+      for (int c = 0; c < n_chunks; ++c) {
+        const int e = c * kCeChunk + tid * 8;
+        if (e < p.V) {
+          if (live) chunk_grad(*(const u32x4*)(row + e), e);
+          else __builtin_nontemporal_store(u32x4{0, 0, 0, 0}, (u32x4*)(grow + e));
         }
       }
     }
+    r = r_next;
+    label = label_next;
   }
 }
 
@@ -197,8 +220,18 @@ __global__ __launch_bounds__(kCeThreads) void ce_reduce_kernel(const CeParams p)
   if (tid == 0) *p.loss_out = acc;
 }
 
+// grid = the workgroups resident at once (a persistent loop over rows; a second round of workgroups
+// would start with an empty pipeline)
 template <int NCH, bool HOLD>
-static void launch_main(const CeParams& p, int grid, hipStream_t s) {
+static void launch_main(const CeParams& p, int n_cu, hipStream_t s) {
+  static int per_cu = 0;  // same on every device of this part
+  if (per_cu == 0) {
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, ce_main_kernel<NCH, HOLD>, kCeThreads, 0) != hipSuccess || n < 1) n = 1;
+    per_cu = n;
+  }
+  const int64_t resident = (int64_t)per_cu * n_cu;
+  const int grid = p.T < resident ? p.T : (int)resident;
   hipLaunchKernelGGL((ce_main_kernel<NCH, HOLD>), dim3(grid), dim3(kCeThreads), 0, s, p);
 }
 
@@ -208,14 +241,13 @@ int launch_packed_ce(const CeParams& p, int n_cu, hipStream_t s, hipEvent_t ev0,
     hipLaunchKernelGGL(ce_weight_kernel, dim3(1), dim3(kCeThreads), 0, s, p);
   }
   if (p.T > 0) {
-    const int grid = p.T < 2 * n_cu ? p.T : 2 * n_cu;  // two workgroups of 16 waves per compute unit
     if (ev0 && hipEventRecord(ev0, s) != hipSuccess) return (int)hipErrorInvalidValue;
     const int chunks = (p.V + kCeChunk - 1) / kCeChunk;
-    if (chunks <= 2) launch_main<2, true>(p, grid, s);
-    else if (chunks <= 4) launch_main<4, true>(p, grid, s);
-    else if (chunks <= 8) launch_main<8, true>(p, grid, s);
-    else if (chunks <= 16) launch_main<16, true>(p, grid, s);
-    else launch_main<1, false>(p, grid, s);
+    if (chunks <= 2) launch_main<2, true>(p, n_cu, s);
+    else if (chunks <= 4) launch_main<4, true>(p, n_cu, s);
+    else if (chunks <= 8) launch_main<8, true>(p, n_cu, s);
+    else if (chunks <= 16) launch_main<16, true>(p, n_cu, s);
+    else launch_main<1, false>(p, n_cu, s);
     if (ev1 && hipEventRecord(ev1, s) != hipSuccess) return (int)hipErrorInvalidValue;
   }
   hipLaunchKernelGGL(ce_reduce_kernel, dim3(1), dim3(kCeThreads), 0, s, p);
