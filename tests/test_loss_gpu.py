@@ -72,11 +72,13 @@ def test_vocab_sizes_around_the_chunk_boundaries(V):
     check(bits, y, cu, 2, t_ave=7.0)
 
 
-def test_llama3_vocab_held_in_registers_and_a_longer_row_streamed_twice():
-    bits, y, cu = make_case([6, 3], 128256, 1)
+def test_large_vocabularies_held_in_registers_and_a_longer_row_streamed_twice():
+    bits, y, cu = make_case([6, 3], 128256, 1)      # 16 chunks of 8192 held per row
     check(bits, y, cu, 0)
-    bits, y, cu = make_case([4, 2], 151936, 2)      # > 131072: two-pass path
+    bits, y, cu = make_case([4, 2], 151936, 2)      # 19 chunks: the 20-chunk form
     check(bits, y, cu, 1)
+    bits, y, cu = make_case([3, 2], 163848, 6)      # > 163840: streamed, running maximum and sum
+    check(bits, y, cu, 2, t_ave=2.0)
 
 
 def test_row_stride_and_more_rows_than_workgroups():
