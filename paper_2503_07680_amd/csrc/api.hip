@@ -92,7 +92,7 @@ extern "C" const char* hbp_status_string(hbp_status s) {
 
 namespace {
 struct CeLayout {
-  size_t weighted_off, token_loss_off, counts_off, weights_off, total;
+  size_t weighted_off, token_loss_off, counts_off, weights_off, row_start_off, total;
 };
 CeLayout ce_layout(int32_t T, int32_t n) {
   CeLayout l;
@@ -100,7 +100,8 @@ CeLayout ce_layout(int32_t T, int32_t n) {
   l.token_loss_off = align_up((size_t)T * sizeof(float), 256);
   l.counts_off = l.token_loss_off + align_up((size_t)T * sizeof(float), 256);
   l.weights_off = l.counts_off + align_up((size_t)n * sizeof(int32_t), 256);
-  l.total = l.weights_off + align_up((size_t)n * sizeof(float), 256) + 256;
+  l.row_start_off = l.weights_off + align_up((size_t)n * sizeof(float), 256);
+  l.total = l.row_start_off + align_up((size_t)(hbp::kCeMaxWorkgroups + 1) * sizeof(int32_t), 256) + 256;
   return l;
 }
 }  // namespace
@@ -143,6 +144,7 @@ extern "C" hbp_status hbp_packed_ce(const void* logits, int64_t logit_stride_t, 
   p.token_loss = token_loss_or_null ? token_loss_or_null : reinterpret_cast<float*>(ws + lay.token_loss_off);
   p.counts = reinterpret_cast<int32_t*>(ws + lay.counts_off);
   p.weights = reinterpret_cast<float*>(ws + lay.weights_off);
+  p.row_start = reinterpret_cast<int32_t*>(ws + lay.row_start_off);
   p.loss_out = loss_out;
   if (hbp::launch_packed_ce(p, kNumCU, static_cast<hipStream_t>(stream), g_events[HBP_LOSS][0],
                             g_events[HBP_LOSS][1]) != 0)

@@ -402,8 +402,10 @@ struct CeParams {  // packed cross-entropy
   float* weighted;     // [T] workspace: w_r CE_r
   int32_t* counts;     // [n_samples] workspace: loss tokens per sample
   float* weights;      // [n_samples] workspace
+  int32_t* row_start;  // [kCeMaxWorkgroups + 1] workspace: first row of every workgroup of the main kernel
   float* loss_out;
 };
+constexpr int kCeMaxWorkgroups = 2048;
 
 // launchers implemented in the .hip files; return hipError_t as int
 // ev0/ev1: optional events recorded around the persistent main kernel

@@ -86,6 +86,22 @@ def test_row_stride_and_more_rows_than_workgroups():
     check(bits, y, cu, 0, stride=520)
 
 
+def test_many_rows_per_workgroup_and_uneven_masking():
+    # several hundred rows per workgroup: the per-row scalars are staged more than once; a long masked
+    # prefix and a dense tail: the ranges of rows per workgroup have very different lengths
+    lens = [50000, 70000, 30000, 50000]
+    bits, y, cu = make_case(lens, 64, 7, p_mask=0.2)
+    y[:90000] = -100
+    y[12345] = 3
+    check(bits, y, cu, 0)
+    check(bits, y, cu, 1)
+    loss, tl, _ = run_gpu(bits, y, cu, 2, t_ave=100.0, want_grad=False)
+    from oracle import loss as L
+    want_loss, want_tl, _ = L.packed_ce(wl.bf16_bits_to_f32(bits).astype(np.float64), y, cu, 2, 100.0)
+    assert np.abs(tl - want_tl).max() <= TOKEN_LOSS_ABS
+    assert abs(loss - want_loss) <= LOSS_REL * abs(want_loss) + 1e-7
+
+
 def test_sample_without_loss_tokens_and_all_masked():
     bits, y, cu = make_case([10, 12, 8], 1024, 4)
     y[10:22] = -1
