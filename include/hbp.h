@@ -267,7 +267,8 @@ hbp_status hbp_packed_ce_workspace_bytes(int32_t total_tokens, int32_t n_samples
  * cu_seqlens int32 [n_samples + 1] with cu_seqlens[0] = 0, cu_seqlens[n_samples] = T;
  * dlogits_or_null bf16 [T, V] dense; loss_out one float; token_loss_or_null float [T] (CE_r, 0 where
  * no label).  V and the stride must be multiples of 8 and the logits 16-byte aligned
- * (HBP_ERR_UNSUPPORTED otherwise).  Rows up to 131072 entries are read once; longer rows twice.
+ * (HBP_ERR_UNSUPPORTED otherwise).  Rows up to 163840 entries are read once; longer rows twice.
+ * A row outside every sample (a cu_seqlens that does not cover [0, T)) gets weight 0.
  * The loss is summed in a fixed order (bit-stable).  Asynchronous on `stream`; allocates nothing.
  * Errors: HBP_ERR_INVALID_ARG (NULL pointers, negative sizes, bad normaliser, t_ave <= 0 for
  * HBP_LOSS_STABLE), HBP_ERR_WORKSPACE, HBP_ERR_DEVICE.  total_tokens = 0 writes loss 0.
