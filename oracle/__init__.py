@@ -9,6 +9,8 @@ from .attention import (attn_fwd, attn_bwd_dq, attn_bwd_dkdv, prob_row, build_or
 from .plan import pack_plan, pack_cost, balance_ratio
 from . import balance_packing
 from . import loss
+from . import auto_selection
 
 __all__ = ["attn_fwd", "attn_bwd_dq", "attn_bwd_dkdv", "prob_row", "build_oracle",
-           "oracle_threads", "pack_plan", "pack_cost", "balance_ratio", "balance_packing", "loss"]
+           "oracle_threads", "pack_plan", "pack_cost", "balance_ratio", "balance_packing", "loss",
+           "auto_selection"]
