@@ -132,6 +132,31 @@ def planner_timing(n=1_000_000):
             "n_batches": int(len(batches)), "metrics": m, "packing_groups": groups}
 
 
+def auto_select_timing():
+    """Host side: Hierarchical Groups Auto-Selection over the paper's candidate lengths and SP degrees with
+    a table profile in the shape of the appendix tables (the library calls back for every profile point;
+    the time is that of the selection logic plus the Python callbacks)."""
+    import paper_2503_07680_amd as H
+    K = 1024
+    best = {8 * K: (2, 8, 2.69), 16 * K: (1, 28, 2.65), 32 * K: (8, 8, 2.83), 64 * K: (4, 28, 3.01),
+            128 * K: (8, 28, 3.05)}
+    calls = [0]
+
+    def memory(l, sp, c):
+        calls[0] += 1
+        return 1.5 * (c - best[l][1]) if sp >= best[l][0] else -5.0
+
+    def iter_time(l, sp, c):
+        calls[0] += 1
+        return best[l][2] * (1.0 + 0.1 * abs(np.log2(sp / best[l][0])))
+
+    t0 = time.perf_counter()
+    groups, per, j = H.hbp_auto_select(sorted(best), [1, 2, 4, 8, 16], 20, 32, memory, iter_time)
+    dt = time.perf_counter() - t0
+    return {"candidate_lengths": sorted(best), "sp_degrees": [1, 2, 4, 8, 16], "profile_calls": calls[0],
+            "seconds": dt, "groups": [int(g["l"]) for g in groups], "group_sp": [int(g["sp"]) for g in groups]}
+
+
 def packed_ce_timing(ev, stream, T=8192, V=128256, n_samples=12, reps=10):
     """The HBM-bound companion kernel: cross-entropy + gradient with the stable normaliser over T tokens
     of a LLaMA-3-sized vocabulary (synthetic logits N(0, 2), 30 % of the tokens without loss).
@@ -298,6 +323,7 @@ def main():
         "busy_time_spread": {"fwd": spread_f, "bwd_dkdv": spread_b, "bwd_dq": spread_q},
     }
     out["balance_packing"] = planner_timing()
+    out["auto_selection"] = auto_select_timing()
     del dev
     out["packed_ce"] = packed_ce_timing(ev, stream)
     if not args.no_cpu_baseline:

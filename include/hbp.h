@@ -241,6 +241,56 @@ hbp_status hbp_balance_packing(const int32_t* lengths, int32_t n_samples,
                                hbp_batch* batches, int32_t batch_cap, int32_t* n_batches_out,
                                hbp_pack_metrics* metrics_or_null);
 
+/* ---- hierarchical groups auto-selection ------------------------------------------------------- */
+
+/*
+ * Profiling is the caller's (this library does not train a model): two callbacks and a context.
+ *   memory(ctx, l, sp, ckpt): REMAINING device memory, any unit, for packing length l, sequence-parallel
+ *                             degree sp and ckpt checkpointed layers; negative = does not fit.
+ *   time(ctx, l, sp, ckpt):   iteration time; NaN, +inf or negative = cannot run.
+ */
+typedef struct {
+  double (*memory)(void* ctx, int32_t l, int32_t sp, int32_t ckpt);
+  double (*time)(void* ctx, int32_t l, int32_t sp, int32_t ckpt);
+  void* ctx;
+} hbp_profile;
+
+/* Stage 1 result for one candidate length: feasible = 0 when no SP degree fits */
+typedef struct {
+  int32_t l, sp, ckpt, feasible;
+  double time;
+} hbp_strategy;
+
+/* one packing group of the result */
+typedef struct {
+  int32_t l, sp, ckpt, reserved;
+} hbp_group;
+
+/*
+ * hbp_auto_select — the paper's Hierarchical Groups Auto-Selection (Section 4.1, Algorithm 1) with
+ * FindBestSpCkpt and GreedyProfileCkpt of the appendix "Implementation Details of Hierarchical Groups
+ * Auto-Selection".  Host only.
+ *   GreedyProfileCkpt(l, sp): m1 = memory(l, sp, c_min), m2 = memory(l, sp, c_max),
+ *       m_ave = (m2 - m1) / (c_max - c_min), c_o = c_max - m2 / m_ave, taken as a layer count:
+ *       ceil, not below 0; m2 < 0: (l, sp) does not fit; m_ave <= 0: 0 if m2 - m_ave c_max >= 0.
+ *   FindBestSpCkpt(l): over sp_set in order, time(l, sp, c_o); the first minimum wins.
+ *   Stage 1: per_length[i] = FindBestSpCkpt(lengths[i]); j = first argmin of the times;
+ *       (s_best, l_best) = entry j, (s_max, l_max) = the last entry (it must be feasible).
+ *   Stage 2: l_1 = floor(l_best / s_best.sp), l_2 = floor(l_max / s_max.sp);
+ *       groups = {l_1, l_best, l_2, l_max} if l_2 > l_best else {l_1, l_best, l_max}, ascending, a
+ *       repeated length reported once.  l_1 and l_2 train with SP 1 and the checkpoint layers of the
+ *       strategy they were derived from; l_best and l_max with their own strategy.
+ * lengths[n_lengths] strictly increasing and positive, sp_set[n_sp] positive, 0 <= c_min < c_max.
+ * Outputs (caller-owned host memory): per_length_or_null[n_lengths], groups[4], *n_groups_out,
+ * *best_index_out_or_null = j.
+ * Errors: HBP_ERR_INVALID_ARG (NULL pointers or callbacks, bad sets or layer counts),
+ * HBP_ERR_UNSUPPORTED when the longest length has no feasible strategy.
+ */
+hbp_status hbp_auto_select(const int32_t* lengths, int32_t n_lengths, const int32_t* sp_set, int32_t n_sp,
+                           int32_t c_min, int32_t c_max, const hbp_profile* profile,
+                           hbp_strategy* per_length_or_null, hbp_group* groups, int32_t* n_groups_out,
+                           int32_t* best_index_out_or_null);
+
 /* ---- packed cross-entropy with the paper's loss normalisers ------------------------------------ */
 
 enum { HBP_LOSS_TOKEN_MEAN = 0, HBP_LOSS_SAMPLE_MEAN = 1, HBP_LOSS_STABLE = 2 };

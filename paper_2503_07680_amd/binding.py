@@ -7,7 +7,7 @@ from __future__ import annotations
 
 import ctypes
 import os
-from typing import Optional, Sequence
+from typing import Callable, Optional, Sequence
 
 import numpy as np
 
@@ -17,12 +17,25 @@ HBP_TILES_QUERY, HBP_TILES_KEY = 0, 1
 EXPORTED_SYMBOLS = ["hbp_status_string", "hbp_pack_plan", "hbp_tile_rows", "hbp_workspace_bytes",
                     "hbp_profile_capacity", "hbp_varlen_attn_fwd", "hbp_varlen_attn_bwd",
                     "hbp_set_kernel_events", "hbp_mfma_probe", "hbp_balance_packing",
-                    "hbp_packed_ce_workspace_bytes", "hbp_packed_ce"]
+                    "hbp_packed_ce_workspace_bytes", "hbp_packed_ce", "hbp_auto_select"]
 
 # numpy views of hbp_pack / hbp_batch
 PACK_DTYPE = np.dtype([("level", "<i4"), ("first_item", "<i4"), ("n_items", "<i4"), ("n_tokens", "<i4"),
                        ("attn_cost", "<i8")])
 BATCH_DTYPE = np.dtype([("level", "<i4"), ("first_pack", "<i4"), ("n_packs", "<i4"), ("reserved", "<i4")])
+
+
+PROFILE_FN = ctypes.CFUNCTYPE(ctypes.c_double, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32)
+
+
+class Profile(ctypes.Structure):
+    """Mirror of ``hbp_profile``."""
+    _fields_ = [("memory", PROFILE_FN), ("time", PROFILE_FN), ("ctx", ctypes.c_void_p)]
+
+
+# numpy views of hbp_strategy / hbp_group
+STRATEGY_DTYPE = np.dtype([("l", "<i4"), ("sp", "<i4"), ("ckpt", "<i4"), ("feasible", "<i4"), ("time", "<f8")])
+GROUP_DTYPE = np.dtype([("l", "<i4"), ("sp", "<i4"), ("ckpt", "<i4"), ("reserved", "<i4")])
 
 
 class PackMetrics(ctypes.Structure):
@@ -99,6 +112,8 @@ def load_library():
                                   vp, ctypes.c_size_t, vp]
     lib.hbp_mfma_probe.restype = i32
     lib.hbp_mfma_probe.argtypes = [i32, i32, vp, vp]
+    lib.hbp_auto_select.restype = i32
+    lib.hbp_auto_select.argtypes = [vp, i32, vp, i32, i32, i32, ctypes.POINTER(Profile), vp, vp, i32p, i32p]
     _lib = lib
     return lib
 
@@ -177,6 +192,34 @@ def hbp_balance_packing(lengths: Sequence[int], group_lens: Sequence[int], packs
     if st != 0:
         raise HbpError(st, "hbp_balance_packing")
     return batches[:n_b.value], packs[:n_p.value], items[:L.size], metrics
+
+
+def hbp_auto_select(lengths: Sequence[int], sp_set: Sequence[int], c_min: int, c_max: int,
+                    profile_memory: Callable, profile_time: Callable):
+    """Hierarchical Groups Auto-Selection.  ``profile_memory(l, sp, ckpt)`` returns the remaining memory
+    (negative: does not fit), ``profile_time(l, sp, ckpt)`` the iteration time (None/inf: cannot run).
+    Returns (groups GROUP_DTYPE[n], per_length STRATEGY_DTYPE[len(lengths)], best_index).  Host only."""
+    lib = load_library()
+    L = np.ascontiguousarray(lengths, dtype=np.int32)
+    S = np.ascontiguousarray(sp_set, dtype=np.int32)
+
+    def mem(_ctx, l, sp, c):
+        return float(profile_memory(l, sp, c))
+
+    def tim(_ctx, l, sp, c):
+        t = profile_time(l, sp, c)
+        return float("inf") if t is None else float(t)
+
+    prof = Profile(PROFILE_FN(mem), PROFILE_FN(tim), None)
+    per = np.zeros(max(int(L.size), 1), dtype=STRATEGY_DTYPE)
+    groups = np.zeros(4, dtype=GROUP_DTYPE)
+    n, j = ctypes.c_int32(), ctypes.c_int32(-1)
+    st = lib.hbp_auto_select(L.ctypes.data if L.size else None, int(L.size), S.ctypes.data if S.size else None,
+                             int(S.size), int(c_min), int(c_max), ctypes.byref(prof), per.ctypes.data,
+                             groups.ctypes.data, ctypes.byref(n), ctypes.byref(j))
+    if st != 0:
+        raise HbpError(st, "hbp_auto_select")
+    return groups[:n.value], per[:L.size], int(j.value)
 
 
 def hbp_tile_rows(d_qk: int, d_v: int, which: int) -> int:

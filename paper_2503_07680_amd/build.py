@@ -12,7 +12,7 @@ CSRC = os.path.join(PKG, "csrc")
 INCLUDE = os.path.join(ROOT, "include")
 LIB = os.path.join(PKG, "libhbp.so")
 OBJ_DIR = os.path.join(PKG, "_build")
-SOURCES = ["api.hip", "fwd.hip", "bwd.hip", "loss.hip", "plan.cpp", "balance.cpp"]
+SOURCES = ["api.hip", "fwd.hip", "bwd.hip", "loss.hip", "plan.cpp", "balance.cpp", "auto_select.cpp"]
 
 HIP_FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-munsafe-fp-atomics", "-Wno-inline-asm",
              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
