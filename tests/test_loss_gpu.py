@@ -86,6 +86,15 @@ def test_row_stride_and_more_rows_than_workgroups():
     check(bits, y, cu, 0, stride=520)
 
 
+@pytest.mark.parametrize("V,T", [(24576, 2400), (128256, 700)])
+def test_several_rows_per_workgroup_with_the_row_held_in_many_chunks(V, T):
+    # the steady state of the chunk pipeline: gradient of one row, refill and statistics of the next,
+    # rows with and without a loss following each other (3 and 16 chunks per row)
+    lens = [T // 3, T // 2, T - T // 3 - T // 2]
+    bits, y, cu = make_case(lens, V, 8 + V % 7)
+    check(bits, y, cu, 2, t_ave=float(T) / 4)
+
+
 def test_many_rows_per_workgroup_and_uneven_masking():
     # several hundred rows per workgroup: the per-row scalars are staged more than once; a long masked
     # prefix and a dense tail: the ranges of rows per workgroup have very different lengths
