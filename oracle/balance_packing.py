@@ -13,7 +13,7 @@ Plain Python integers and lists, every step written as the paper states it, in t
   sort the packs by a, cut consecutive packs into mini-batches.
 * Metrics (Section 3.1): DBR, PR, ABR, CR, Ave-T equations.
 
-Readings where the paper is silent (the same ones the C++ planner takes; listed in the design doc):
+Readings where the paper is silent (the same ones the C++ planner takes):
   - Packing: "arbitrary packing methods are feasible" -> first-fit decreasing: samples by length
     descending (ties: input order), each into the first pack (in creation order) it fits.
   - Sort direction and ties: a descending, ties by pack creation order.
