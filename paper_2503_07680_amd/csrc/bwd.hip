@@ -66,7 +66,7 @@ __global__ __launch_bounds__(kThreads, DQK <= 128 ? 2 : 1) void bwd_dq_kernel(co
   constexpr int NC = DQK / 16, NCV = DV / 16, NDB = DQK / 32;
   constexpr int PD = 4;
   // Scores in the vector file (asm MFMA) only where the kernel compiles without spills.
-  constexpr bool kVgprScores = DQK <= 128;
+  constexpr bool kVgprScores = true;
 
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   // [K buf0][K buf1][V buf0][V buf1]
@@ -463,7 +463,6 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
       constexpr int kPD = 3;  // LDS read-ahead depth (fragments)
       auto do_step = [&](int step) {
         const int qb = qb_start + (step % nqb) * BQ;
-        if (!wave_active || qb + BQ - 1 < kw0_in) return;  // block lies above this wave's keys
         auto sd_load = [&](int sub) {
           return [&, sub](int i) {
             Frag a;
@@ -475,7 +474,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
         // The asm form (scores produced in the vector file) is only used where the kernel compiles
         // without register spills: spill copies next to an asm MFMA would bypass the compiler's
         // hazard handling.  d_qk = 192 spills, so it takes the builtin (slower, always safe).
-        constexpr bool kVgprScores = DQK <= 128;
+        constexpr bool kVgprScores = true;
         auto sd_mma = [&](Sub& x) {
           return [&](int i, const Frag& a) {
             if (kVgprScores) {
@@ -565,22 +564,17 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
           }
           if (i > 0) stage2(x, sub, i - 1, e_prev, dd_prev, masked);
         };
-        auto run_single = [&](int sub) {
-          Sub x;
-          LdsChain<NC + NCV, kPD> c1;
-          c1.prefill(sd_load(sub));
-          c1.run(sd_load(sub), sd_mma(x));
-          LdsChain<2 * NEB + 2 * NDB, kPD> c2;
-          rows_prefetch(sub, 0);
-          c2.prefill(gr_load(sub));
-          if (kVgprScores) mfma_results_ready(x.s, x.dp);
-#pragma unroll
-          for (int i = 0; i < 17; ++i) sm_slice(x, sub, i, std::true_type{});
-          __builtin_amdgcn_sched_barrier(0);
-          c2.run(gr_load(sub), gr_mma(x));
-        };
-        auto run_pair = [&]() {
-          Sub xa, xb;
+        // Every update of the dK^T / dV^T accumulators of a step is issued from ONE place (the two gr
+        // chains at the end), whatever path computed the probabilities: with updates in several
+        // branches the compiler keeps a second set of the 128 accumulator registers and copies one
+        // set to the other in every step (one vector instruction per register).
+        const bool in_reach = wave_active && qb + BQ - 1 >= kw0_in;  // else: block lies above this wave's keys
+        const bool need_a = in_reach && qb + 31 >= kw0_in;           // qb < s_len always holds
+        const bool need_b = in_reach && qb + 63 >= kw0_in && qb + 32 < s_len;
+        const bool any_mask = kw0_in + 31 > qb || qb + 63 >= s_len;  // diagonal or sample tail in reach
+        const bool pair = need_a && need_b && !any_mask;
+        Sub xa, xb;
+        if (pair) {
           LdsChain<NC + NCV, kPD> c1;
           c1.prefill(sd_load(0));
           c1.run(sd_load(0), sd_mma(xa));
@@ -589,24 +583,52 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
           if (kVgprScores) mfma_results_ready(xa.s, xa.dp);
           c1.template run_with<16>(sd_load(1), sd_mma(xb), [&](int i) { sm_slice(xa, 0, i, std::false_type{}); });
           sm_slice(xa, 0, 16, std::false_type{});
-          LdsChain<2 * NEB + 2 * NDB, kPD> c2;
-          rows_prefetch(1, 0);
-          c2.prefill(gr_load(0));
-          if (kVgprScores) mfma_results_ready(xb.s, xb.dp);
-          c2.template run_with<16>(gr_load(0), gr_mma(xa), [&](int i) { sm_slice(xb, 1, i, std::false_type{}); });
-          sm_slice(xb, 1, 16, std::false_type{});
-          c2.prefill(gr_load(1));
-          c2.run(gr_load(1), gr_mma(xb));
-        };
-        const bool need_a = qb + 31 >= kw0_in;                      // qb < s_len always holds
-        const bool need_b = qb + 63 >= kw0_in && qb + 32 < s_len;
-        const bool any_mask = kw0_in + 31 > qb || qb + 63 >= s_len;  // diagonal or sample tail in reach
-        if (need_a && need_b && !any_mask) {
-          run_pair();
         } else {
-          if (need_a) run_single(0);
-          if (need_b) run_single(1);
+          // sub-block A: masked, finished here.  Sub-block B: its probabilities are formed by the same
+          // unmasked slices as on the fast path (behind the first gr chain below), so the mask goes
+          // into the scores instead: -inf gives exp2 = 0 (the scale is positive) and dS = 0 (dP - D).
+          if (need_a) {
+            LdsChain<NC + NCV, kPD> c1;
+            c1.prefill(sd_load(0));
+            c1.run(sd_load(0), sd_mma(xa));
+            rows_prefetch(0, 0);
+            if (kVgprScores) mfma_results_ready(xa.s, xa.dp);
+#pragma unroll
+            for (int i = 0; i < 17; ++i) sm_slice(xa, 0, i, std::true_type{});
+          } else {
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+              xa.pb[j].u = u32x4{0, 0, 0, 0};
+              xa.dsb[j].u = u32x4{0, 0, 0, 0};
+            }
+          }
+          if (need_b) {
+            LdsChain<NC + NCV, kPD> c1;
+            c1.prefill(sd_load(1));
+            c1.run(sd_load(1), sd_mma(xb));
+            if (kVgprScores) mfma_results_ready(xb.s, xb.dp);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const int q_in = qb + 32 + 8 * (i >> 2) + 4 * hh + (i & 3);
+              if (key_in > q_in || q_in >= s_len) xb.s[i] = -INFINITY;
+            }
+          } else {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              xb.s[i] = -INFINITY;
+              xb.dp[i] = 0.f;
+            }
+          }
         }
+        rows_prefetch(1, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        LdsChain<2 * NEB + 2 * NDB, kPD> c2;
+        c2.prefill(gr_load(0));
+        if (kVgprScores) mfma_results_ready(xb.s, xb.dp);
+        c2.template run_with<16>(gr_load(0), gr_mma(xa), [&](int i) { sm_slice(xb, 1, i, std::false_type{}); });
+        sm_slice(xb, 1, 16, std::false_type{});
+        c2.prefill(gr_load(1));
+        c2.run(gr_load(1), gr_mma(xb));
       };
 
       int cur_buf = 0;
