@@ -344,8 +344,8 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
 
-  // Absolute LDS addresses of this lane's fragments: workgroup base and current buffer included
-  // (toggled once per step), so a read needs no address arithmetic.
+  // Absolute LDS addresses of this lane's fragments in buffer 0 (workgroup base included): a read
+  // needs no address arithmetic, the buffer and the sub-block go into its immediate offset.
   const uint32_t lds0 = lds_address(smem);
   uint32_t qoff[NC], dooff[NCV], qtoff[2][NDB], dotoff[2][NEB];
 #pragma unroll
@@ -378,6 +378,12 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
   FullTileLoader<DV, BQ> o_loader;
   q_loader.init(wave, lane, q_stride_b);
   o_loader.init(wave, lane, o_stride_b);
+
+  // Both tile buffers start out as zeros: an idle step (see the step loop) multiplies whatever the
+  // second buffer holds by zero operands, and that must not be the NaN patterns of unwritten LDS.
+  for (int i = tid * 16; i < 2 * Q_TILE + 2 * O_TILE + 4 * BQ * (int)sizeof(float); i += kThreads * 16)
+    *(u32x4*)(smem + i) = u32x4{0, 0, 0, 0};
+  __syncthreads();
 
   ProfAcc pa;
   const WorkQueues wq{p.counter, p.n_tiles, p.Hkv, 1};
@@ -455,19 +461,21 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
       // other's MFMAs (the matrix pipe leaves about half of each MFMA's issue time free):
       //     sd(A) | sd(B) + sm(A) | gr(A) + sm(B) | gr(B)
       // Blocks that touch the diagonal or the sample tail take the plain masked path.
-      // All LDS offsets already contain the current buffer's base (toggled once per step).
       struct Sub {
         f32x16 s, dp;
         Frag pb[2], dsb[2];
       };
       constexpr int kPD = 3;  // LDS read-ahead depth (fragments)
-      auto do_step = [&](int step) {
+      auto do_step = [&](int step, auto buf_tag) {
+        // the step's buffer is a compile-time constant: it goes into the immediate offset of every LDS
+        // read (two copies of the step's code instead of 34 address updates per step)
+        constexpr int BUF = decltype(buf_tag)::value;
         const int qb = qb_start + (step % nqb) * BQ;
         auto sd_load = [&](int sub) {
           return [&, sub](int i) {
             Frag a;
-            if (i < NC) a.u = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(qoff[i] + 32 * sub * QRB);
-            else a.u = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(dooff[i - NC] + 32 * sub * ORB);
+            if (i < NC) a.u = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(qoff[i] + 32 * sub * QRB + BUF * Q_TILE);
+            else a.u = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(dooff[i - NC] + 32 * sub * ORB + BUF * O_TILE);
             return a;
           };
         };
@@ -502,12 +510,12 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
             Frag a;
             if (i < 2 * NEB) {
               const int eb = i % NEB, j = i / NEB;
-              const uint32_t base = (32 * sub + 16 * j) * ORB;
+              const uint32_t base = (32 * sub + 16 * j) * ORB + BUF * O_TILE;
               a.h[0] = lds_read_tr16_at(dotoff[0][eb] + base);
               a.h[1] = lds_read_tr16_at(dotoff[1][eb] + base);
             } else {
               const int db = (i - 2 * NEB) % NDB, j = (i - 2 * NEB) / NDB;
-              const uint32_t base = (32 * sub + 16 * j) * QRB;
+              const uint32_t base = (32 * sub + 16 * j) * QRB + BUF * Q_TILE;
               a.h[0] = lds_read_tr16_at(qtoff[0][db] + base);
               a.h[1] = lds_read_tr16_at(qtoff[1][db] + base);
             }
@@ -529,8 +537,8 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
         float e_cur = 0.f, d_prev = 0.f;      // exp of element i (stage 1), D of the element in stage 2
         float pr_even = 0.f, ds_even = 0.f;
         auto rows_prefetch = [&](int sub, int b) {
-          l4n = *(const __attribute__((address_space(3))) f32x4*)(uintptr_t)(lseoff + (32 * sub + 8 * b) * 4);
-          d4n = *(const __attribute__((address_space(3))) f32x4*)(uintptr_t)(dvoff + (32 * sub + 8 * b) * 4);
+          l4n = *(const __attribute__((address_space(3))) f32x4*)(uintptr_t)(lseoff + (32 * sub + 8 * b + BUF * BQ) * 4);
+          d4n = *(const __attribute__((address_space(3))) f32x4*)(uintptr_t)(dvoff + (32 * sub + 8 * b + BUF * BQ) * 4);
         };
         auto stage2 = [&](Sub& x, int sub, int i, float e_val, float d_val, auto masked) {
           const int b = i >> 2, v = i & 3;
@@ -568,7 +576,8 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
         // chains at the end), whatever path computed the probabilities: with updates in several
         // branches the compiler keeps a second set of the 128 accumulator registers and copies one
         // set to the other in every step (one vector instruction per register).
-        const bool in_reach = wave_active && qb + BQ - 1 >= kw0_in;  // else: block lies above this wave's keys
+        // else: block lies above this wave's keys, or this is the idle step that makes the count even
+        const bool in_reach = wave_active && step < n_steps && qb + BQ - 1 >= kw0_in;
         const bool need_a = in_reach && qb + 31 >= kw0_in;           // qb < s_len always holds
         const bool need_b = in_reach && qb + 63 >= kw0_in && qb + 32 < s_len;
         const bool any_mask = kw0_in + 31 > qb || qb + 63 >= s_len;  // diagonal or sample tail in reach
@@ -631,45 +640,18 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
         c2.run(gr_load(1), gr_mma(xb));
       };
 
-      int cur_buf = 0;
-      for (int step = 0; step < n_steps; ++step) {
+      // Two steps per iteration, one on each buffer, with no branch between them: the accumulators are
+      // updated at two places that follow each other, never on alternative paths.  An odd number of
+      // steps is rounded up by an idle step (zero operands).
+      for (int step = 0; step < n_steps; step += 2) {
         wait_async_loads();
         __syncthreads();
         if (step + 1 < n_steps) issue(step + 1);
-        if ((step & 1) != cur_buf) {  // point every LDS offset at this step's buffer
-          const int dq_ = (step & 1) ? Q_TILE : -Q_TILE, do_ = (step & 1) ? O_TILE : -O_TILE;
-          const int dr_ = (step & 1) ? BQ * 4 : -BQ * 4;
-#pragma unroll
-          for (int c = 0; c < NC; ++c) qoff[c] += dq_;
-#pragma unroll
-          for (int c = 0; c < NCV; ++c) dooff[c] += do_;
-#pragma unroll
-          for (int r = 0; r < 2; ++r) {
-#pragma unroll
-            for (int db = 0; db < NDB; ++db) qtoff[r][db] += dq_;
-#pragma unroll
-            for (int eb = 0; eb < NEB; ++eb) dotoff[r][eb] += do_;
-          }
-          lseoff += dr_;
-          dvoff += dr_;
-          cur_buf = step & 1;
-        }
-        do_step(step);
-      }
-      if (cur_buf) {  // leave the offsets on buffer 0 for the next item
-#pragma unroll
-        for (int c = 0; c < NC; ++c) qoff[c] -= Q_TILE;
-#pragma unroll
-        for (int c = 0; c < NCV; ++c) dooff[c] -= O_TILE;
-#pragma unroll
-        for (int r = 0; r < 2; ++r) {
-#pragma unroll
-          for (int db = 0; db < NDB; ++db) qtoff[r][db] -= Q_TILE;
-#pragma unroll
-          for (int eb = 0; eb < NEB; ++eb) dotoff[r][eb] -= O_TILE;
-        }
-        lseoff -= BQ * 4;
-        dvoff -= BQ * 4;
+        do_step(step, std::integral_constant<int, 0>{});
+        wait_async_loads();
+        __syncthreads();
+        if (step + 2 < n_steps) issue(step + 2);
+        do_step(step + 1, std::integral_constant<int, 1>{});
       }
 
       if (key_valid) {
