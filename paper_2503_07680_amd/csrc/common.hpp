@@ -81,16 +81,26 @@ __device__ __forceinline__ float max_with_other_half(float x) {
 }
 
 // ---- LDS tiles in their natural [row][dim] layout, 16-byte chunks XOR-swizzled -----------------
-// Chunk c of row r sits at chunk position c ^ (g(r) & MASK), g(r) = ((r&3)<<2) | ((r>>2)&3).
-// With 256-byte rows this serves both access patterns without bank conflicts: 16 consecutive
-// rows read at one chunk index (row-major MFMA operand, 16-byte reads) hit 16 distinct chunk
-// positions, and the 8 rows x 4 consecutive chunks of one transposing read spread over all four
-// 64-byte quarters of the bank line twice.
+// Chunk c of row r sits at chunk position c ^ f(r).  Two access patterns have to stay free of bank
+// conflicts (a bank line is 16 chunks): 16 consecutive rows read at one chunk index (row-major MFMA
+// operand, 16-byte reads), and the 4 rows x 4 consecutive chunks that one half of a transposing read
+// touches.
+//  * 256-byte rows (16 chunks): a row starts at bank 0, so f must take 16 values over 16 rows and
+//    separate the 4 rows of a transposing read into the four quarters of the line:
+//    f(r) = ((r&3)<<2) | ((r>>2)&3).
+//  * 128- and 384-byte rows (8 or 24 chunks): rows alternate between the two halves of the bank line
+//    (r*8 mod 16), so only the low three chunk bits may be permuted (the result must stay inside the
+//    row) and f must be a bijection onto 0..7 over the 8 even rows of a 16-row window (same for the
+//    odd rows), with the two even (odd) rows of every aligned group of four differing in bit 2:
+//    f(r) = (bit1(r)<<2) | (bit3(r)<<1) | bit2(r).
+//    (Taking the 16-chunk f modulo 8 instead gave two-way conflicts on 33-43 % of the LDS cycles of
+//    the d_qk = 192 kernels.)
 __device__ __forceinline__ int swz_g(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
+__device__ __forceinline__ int swz_h(int row) { return (((row >> 1) & 1) << 2) | (((row >> 3) & 1) << 1) | ((row >> 2) & 1); }
 template <int D>
 __device__ __forceinline__ int swz(int chunk, int row) {
-  constexpr int MASK = (D / 8 == 16) ? 15 : 7;
-  return chunk ^ (swz_g(row) & MASK);
+  static_assert(D / 8 == 16 || D / 8 == 8 || D / 8 == 24, "row of 8, 16 or 24 chunks");
+  return chunk ^ (D / 8 == 16 ? swz_g(row) : swz_h(row));
 }
 
 // Asynchronous global -> LDS copy of a [ROWS][D] bf16 tile (row stride `stride` elements), with
