@@ -461,6 +461,8 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
         for (int c = 0; c < NC; ++c) knat[c].u = key_valid ? *(const u32x4*)(kp + 16 * c) : u32x4{0, 0, 0, 0};
 #pragma unroll
         for (int c = 0; c < NCV; ++c) vnat[c].u = key_valid ? *(const u32x4*)(vp + 16 * c) : u32x4{0, 0, 0, 0};
+#pragma unroll
+        for (int c = 0; c < NCV; ++c) vnat[c].u ^= u32x4{0x80008000u, 0x80008000u, 0x80008000u, 0x80008000u};
       }
       f32x16 dkt[NDB], dvt[NEB];
 #pragma unroll
@@ -505,7 +507,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
             if (kVgprScores) {
               if (i == 0) x.s = mfma32_vgpr_first(a.v, knat[0].v);
               else if (i < NC) mfma32_vgpr(x.s, a.v, knat[i].v);
-              else if (i == NC) x.dp = mfma32_vgpr_first(a.v, vnat[0].v);
+              else if (i == NC) mfma32_vgpr(x.dp, a.v, vnat[0].v);
               else mfma32_vgpr(x.dp, a.v, vnat[i - NC].v);
             } else {
               if (i == 0 || i == NC) {
@@ -546,25 +548,36 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
           };
         };
         // element i = 4b+v of the accumulators <-> query q0 + 8b + 4hh + v, key column key_in.
-        // The per-element arithmetic  pr = exp2(c*s - lse2);  ds = pr * (dp - D)  is issued in two
+        // The per-element arithmetic  pr = exp2(c*s - lse2);  ds = pr * (D - dP)  is issued in two
         // stages one slice apart (stage 1 of element i next to stage 2 of element i-1), so that no
-        // vector instruction waits on the one just before it; LSE2 / D of the 4 query rows of group
-        // b are read from LDS one group ahead (rows_prefetch(sub, 0) before the chain).
-        f32x4 l4, d4, l4n, d4n;
-        float e_cur = 0.f, d_prev = 0.f;      // exp of element i (stage 1), D of the element in stage 2
+        // vector instruction waits on the one just before it; LSE2 of the 4 query rows of group b is
+        // read from LDS one group ahead (rows_prefetch(sub, 0) before the chain).  D - dP comes
+        // straight out of the MFMAs: the accumulator starts as D (init_dp) and V is held negated, so
+        // no subtraction is left for the vector unit; dS and dK carry the opposite sign until the
+        // final scaling.
+        f32x4 l4, l4n;
+        float e_cur = 0.f;  // exp of element i (stage 1)
         float pr_even = 0.f, ds_even = 0.f;
         auto rows_prefetch = [&](int sub, int b) {
           l4n = *(const __attribute__((address_space(3))) f32x4*)(uintptr_t)(lseoff + (32 * sub + 8 * b + BUF * BQ) * 4);
-          d4n = *(const __attribute__((address_space(3))) f32x4*)(uintptr_t)(dvoff + (32 * sub + 8 * b + BUF * BQ) * 4);
         };
-        auto stage2 = [&](Sub& x, int sub, int i, float e_val, float d_val, auto masked) {
+        // the dP accumulator of a sub-block starts as D (V is held negated: it ends as D - dP)
+        auto init_dp = [&](Sub& x, int sub) {
+#pragma unroll
+          for (int b = 0; b < 4; ++b) {
+            const f32x4 t = *(const __attribute__((address_space(3))) f32x4*)(uintptr_t)(dvoff + (32 * sub + 8 * b + BUF * BQ) * 4);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) x.dp[4 * b + v] = t[v];
+          }
+        };
+        auto stage2 = [&](Sub& x, int sub, int i, float e_val, auto masked) {
           const int b = i >> 2, v = i & 3;
           float pr = e_val;
           if (decltype(masked)::value) {
             const int q_in = qb + 32 * sub + 8 * b + 4 * hh + v;
             if (key_in > q_in || q_in >= s_len) pr = 0.f;
           }
-          const float ds = pr * (x.dp[i] - d_val);
+          const float ds = pr * x.dp[i];
           if (i & 1) {
             x.pb[b >> 1].w[2 * (b & 1) + (v >> 1)] = pack_bf16(pr_even, pr);
             x.dsb[b >> 1].w[2 * (b & 1) + (v >> 1)] = pack_bf16(ds_even, ds);
@@ -576,18 +589,15 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
         // slices 0..16: slice i runs stage 1 of element i (i < 16) and stage 2 of element i-1 (i > 0)
         auto sm_slice = [&](Sub& x, int sub, int i, auto masked) {
           const float e_prev = e_cur;
-          const float dd_prev = d_prev;
           if (i < 16) {
             const int b = i >> 2, v = i & 3;
             if (v == 0) {
               l4 = l4n;
-              d4 = d4n;
               if (b < 3) rows_prefetch(sub, b + 1);
             }
             e_cur = __builtin_amdgcn_exp2f(__builtin_fmaf(x.s[i], p.scale_log2, -l4[v]));
-            d_prev = d4[v];
           }
-          if (i > 0) stage2(x, sub, i - 1, e_prev, dd_prev, masked);
+          if (i > 0) stage2(x, sub, i - 1, e_prev, masked);
         };
         // Every update of the dK^T / dV^T accumulators of a step is issued from ONE place (the two gr
         // chains at the end), whatever path computed the probabilities: with updates in several
@@ -602,9 +612,11 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
         Sub xa, xb;
         if (pair) {
           LdsChain<NC + NCV, kPD> c1;
+          init_dp(xa, 0);
           c1.prefill(sd_load(0));
           c1.run(sd_load(0), sd_mma(xa));
           rows_prefetch(0, 0);
+          init_dp(xb, 1);
           c1.prefill(sd_load(1));
           if (kVgprScores) mfma_results_ready(xa.s, xa.dp);
           c1.template run_with<16>(sd_load(1), sd_mma(xb), [&](int i) { sm_slice(xa, 0, i, std::false_type{}); });
@@ -615,6 +627,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
           // into the scores instead: -inf gives exp2 = 0 (the scale is positive) and dS = 0 (dP - D).
           if (need_a) {
             LdsChain<NC + NCV, kPD> c1;
+            init_dp(xa, 0);
             c1.prefill(sd_load(0));
             c1.run(sd_load(0), sd_mma(xa));
             rows_prefetch(0, 0);
@@ -630,6 +643,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
           }
           if (need_b) {
             LdsChain<NC + NCV, kPD> c1;
+            init_dp(xb, 1);
             c1.prefill(sd_load(1));
             c1.run(sd_load(1), sd_mma(xb));
             if (kVgprScores) mfma_results_ready(xb.s, xb.dp);
@@ -678,8 +692,9 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
         for (int db = 0; db < NDB; ++db)
 #pragma unroll
           for (int b = 0; b < 4; ++b) {
-            u32x2 w = {pack_bf16(dkt[db][4 * b] * p.scale, dkt[db][4 * b + 1] * p.scale),
-                       pack_bf16(dkt[db][4 * b + 2] * p.scale, dkt[db][4 * b + 3] * p.scale)};
+            const float ksc = -p.scale;
+            u32x2 w = {pack_bf16(dkt[db][4 * b] * ksc, dkt[db][4 * b + 1] * ksc),
+                       pack_bf16(dkt[db][4 * b + 2] * ksc, dkt[db][4 * b + 3] * ksc)};
             *(u32x2*)(dkp + 32 * db + 8 * b) = w;
           }
 #pragma unroll
