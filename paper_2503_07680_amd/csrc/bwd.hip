@@ -65,7 +65,8 @@ __global__ __launch_bounds__(kThreads, DQK <= 128 ? 2 : 1) void bwd_dq_kernel(co
   constexpr int K_TILE = BN * KRB, V_TILE = BN * VRB;
   constexpr int NC = DQK / 16, NCV = DV / 16, NDB = DQK / 32;
   constexpr int PD = 4;
-  // Scores in the vector file (asm MFMA) only where the kernel compiles without spills.
+  // Scores in the vector file (asm MFMA): needs a kernel that compiles without spills (checked at build
+  // time); the builtin form stays as the fallback.
   constexpr bool kVgprScores = true;
 
   extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -498,9 +499,10 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
             return a;
           };
         };
-        // The asm form (scores produced in the vector file) is only used where the kernel compiles
-        // without register spills: spill copies next to an asm MFMA would bypass the compiler's
-        // hazard handling.  d_qk = 192 spills, so it takes the builtin (slower, always safe).
+        // The asm form (scores produced in the vector file) needs a kernel that compiles without
+        // register spills: spill copies next to an asm MFMA would bypass the compiler's hazard
+        // handling.  Every instantiation does (a build-time test checks it); the builtin form stays
+        // as the fallback should one stop doing so.
         constexpr bool kVgprScores = true;
         auto sd_mma = [&](Sub& x) {
           return [&](int i, const Frag& a) {
