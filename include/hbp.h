@@ -333,8 +333,10 @@ hbp_status hbp_packed_ce(const void* logits, int64_t logit_stride_t, int32_t tot
  * one kernel in which every SIMD of `n_cu` compute units (two wavefronts each) issues nothing but
  * independent 32x32x16 bf16 MFMAs on register-resident data: `mfma_per_wave` of them per wavefront
  * (rounded down to a multiple of 4).  The caller times the launch (events on the same stream);
- * executed flops = n_cu * 8 * mfma_per_wave * 32768.  That rate is what the matrix pipes of this
- * part sustain under its power limit, i.e. the practical ceiling next to the published peak.
+ * executed flops = n_cu * 8 * mfma_per_wave * 32768.  The operands are pseudo-random bf16 values of
+ * magnitude 0.5 .. 1 with random signs (with constants the part clocks higher and the figure comes out
+ * about a fifth larger).  That rate is what the matrix pipes of this part sustain under its power
+ * limit on such data, i.e. the practical ceiling next to the published peak.
  * `sink` (device, >= n_cu * 512 floats) receives one value per thread so the work is not removed;
  * it carries no information.  Returns HBP_ERR_INVALID_ARG for NULL sink, n_cu < 1 or
  * mfma_per_wave < 4, HBP_ERR_DEVICE if the launch fails.  Asynchronous; allocates nothing.

@@ -153,13 +153,22 @@ extern "C" hbp_status hbp_packed_ce(const void* logits, int64_t logit_stride_t, 
 }
 
 namespace {
-// nothing but independent MFMAs: four accumulators per wave, operands in registers
+// nothing but independent MFMAs: four accumulators per wave, operands in registers.  The operands are
+// pseudo-random bf16 values of magnitude 0.5 .. 1 with random signs: what the matrix pipes sustain
+// depends on the data (the part is power-limited), and constants would flatter the figure by a fifth.
 __global__ __launch_bounds__(512) void mfma_probe_kernel(float* sink, int n_groups) {
-  hbp::bf16x8 a, b;
+  hbp::Frag a, b;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    a[i] = (__bf16)(threadIdx.x * 0.001f + i);
-    b[i] = (__bf16)(0.5f + blockIdx.x * 0.01f);
+  for (int i = 0; i < 4; ++i) {
+    uint32_t h = (uint32_t)(blockIdx.x * 512 + threadIdx.x) * 4u + (uint32_t)i;
+    h *= 2654435761u;
+    h ^= h >> 15;
+    h *= 2246822519u;
+    h ^= h >> 13;
+    a.w[i] = (h & 0x807f807fu) | 0x3f003f00u;
+    h *= 3266489917u;
+    h ^= h >> 16;
+    b.w[i] = (h & 0x807f807fu) | 0x3f003f00u;
   }
   hbp::f32x16 c[4];
 #pragma unroll
@@ -168,7 +177,7 @@ __global__ __launch_bounds__(512) void mfma_probe_kernel(float* sink, int n_grou
     for (int i = 0; i < 16; ++i) c[j][i] = 0.f;
   for (int it = 0; it < n_groups; ++it) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) c[j] = hbp::mfma32(a, b, c[j]);
+    for (int j = 0; j < 4; ++j) c[j] = hbp::mfma32(a.v, b.v, c[j]);
   }
   sink[blockIdx.x * blockDim.x + threadIdx.x] = c[0][3] + c[1][3] + c[2][3] + c[3][3];
 }
