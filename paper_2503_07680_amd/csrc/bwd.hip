@@ -416,18 +416,22 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
       const int nqb = (s_len - qb_start + BQ - 1) / BQ;
       const int n_steps = nqb * p.g;
 
-      // Copies of the steps' blocks are issued in step order; the source pointers of the next block to
-      // copy are carried along (a block further down the head, or the first block of the next head)
-      // instead of being recomputed from the step number: a handful of scalar instructions per step.
-      const uint16_t* q_src = p.q + (int64_t)(s0 + qb_start) * p.q_st + (int64_t)(kh * p.g) * p.q_sh;
-      const uint16_t* o_src = p.d_o + (int64_t)(s0 + qb_start) * p.o_st + (int64_t)(kh * p.g) * p.o_sh;
-      const float* row_src = (wave == 0 ? p.lse2 : p.D) + (int64_t)(kh * p.g) * p.T + s0 + qb_start;
-      const uint16_t* q_head = q_src;
-      const uint16_t* o_head = o_src;
-      const float* row_head = row_src;
-      int blk_next = 0;
+      // Step order: the query blocks from the LAST one of the sample down to the tile's own, and for each
+      // block the g query heads of the group.  Every key tile of a sample needs a suffix of the same
+      // blocks, so the workgroups of a die (they work on tiles of the same kv head) ask for the same
+      // block at about the same time and it comes from that die's L2 once, not from HBM once per tile.
+      // Copies are issued in step order; the source pointers of the next block to copy are carried
+      // along instead of being recomputed from the step number.
+      const int64_t last_row = (int64_t)s0 + qb_start + (int64_t)(nqb - 1) * BQ;
+      const uint16_t* q_blk = p.q + last_row * p.q_st + (int64_t)(kh * p.g) * p.q_sh;
+      const uint16_t* o_blk = p.d_o + last_row * p.o_st + (int64_t)(kh * p.g) * p.o_sh;
+      const float* row_blk = (wave == 0 ? p.lse2 : p.D) + (int64_t)(kh * p.g) * p.T + last_row;
+      const uint16_t* q_src = q_blk;
+      const uint16_t* o_src = o_blk;
+      const float* row_src = row_blk;
+      int blk_next = nqb - 1, head_next = 0;
       auto issue_next = [&](int buf) {
-        const int valid = s_len - qb_start - blk_next * BQ;  // >= 1
+        const int valid = s_len - qb_start - blk_next * BQ;  // >= 1; < BQ only for the sample's last block
         q_loader.issue(q_src, q_stride_b, valid, q_lds + buf * Q_TILE, wave, lane);
         o_loader.issue(o_src, o_stride_b, valid, o_lds + buf * O_TILE, wave, lane);
         if (wave < 2) {
@@ -437,18 +441,19 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
           const float* dst = (wave == 0 ? lse_lds : d_lds) + buf * BQ;
           async_copy4(row_src, (uint32_t)row * 4u, lds_address(dst));
         }
-        if (++blk_next == nqb) {  // on to the next query head of the group
-          blk_next = 0;
-          q_head += p.q_sh;
-          o_head += p.o_sh;
-          row_head += p.T;
-          q_src = q_head;
-          o_src = o_head;
-          row_src = row_head;
+        if (++head_next == p.g) {  // on to the block before
+          head_next = 0;
+          --blk_next;
+          q_blk -= (int64_t)BQ * p.q_st;
+          o_blk -= (int64_t)BQ * p.o_st;
+          row_blk -= BQ;
+          q_src = q_blk;
+          o_src = o_blk;
+          row_src = row_blk;
         } else {
-          q_src += (int64_t)BQ * p.q_st;
-          o_src += (int64_t)BQ * p.o_st;
-          row_src += BQ;
+          q_src += p.q_sh;
+          o_src += p.o_sh;
+          row_src += p.T;
         }
       };
       if (n_steps > 0) issue_next(0);
@@ -490,7 +495,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
         // the step's buffer is a compile-time constant: it goes into the immediate offset of every LDS
         // read (two copies of the step's code instead of 34 address updates per step)
         constexpr int BUF = decltype(buf_tag)::value;
-        const int qb = qb_start + (step % nqb) * BQ;
+        const int qb = qb_start + (nqb - 1 - step / p.g) * BQ;
         auto sd_load = [&](int sub) {
           return [&, sub](int i) {
             Frag a;
