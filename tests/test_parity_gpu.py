@@ -94,3 +94,77 @@ def test_config4_long_128k_sampled():
                       + [int(x) for x in rng.integers(0, 131072, 40)]))
     cols = list(range(98304 - 96, 98304)) + list(range(131072 - 96, 131072)) + [131072 - 300]
     compare(case, pa, out, q_heads=list(range(24, 32)), rows=rows, cols=sorted(set(cols)), label="kv-group 3")
+
+
+@pytest.mark.parametrize("Hq,Hkv,d,e,pad_h", [(4, 2, 128, 128, 0), (2, 2, 64, 64, 8), (2, 1, 192, 128, 16)])
+def test_strided_views_of_fused_buffers(Hq, Hkv, d, e, pad_h):
+    """Q, K, V as column slices of one fused [T, W] projection buffer (and dQ, dK, dV of one fused
+    gradient buffer), O and dO with padded heads: the descriptor's strides carry the layout.
+    Results must equal the dense-layout run bit for bit, meet the oracle's bars, and no element
+    outside the views may change."""
+    import copy
+    import torch
+    from paper_2503_07680_amd import binding as B
+    case = Case([150, 1, 290, 64, 33], 538, Hq, Hkv, d, e, seed=31, name="strided")
+    pa, dev, dense = run_gpu(case)
+    T, bf = pa.T, torch.bfloat16
+    qh, kh, vh, oh = d + pad_h, d + pad_h, e + pad_h, e + pad_h      # head strides (elements)
+    wq, wk, wv = Hq * qh, Hkv * kh, Hkv * vh
+    W = wq + wk + wv + 24                                            # row stride of the fused buffer
+    sentinel = 1.5
+    fused = torch.full((T, W), sentinel, dtype=bf, device=pa.device)
+    grads = torch.full((T, W), sentinel, dtype=bf, device=pa.device)
+    o_buf = torch.full((T, Hq * oh + 8), sentinel, dtype=bf, device=pa.device)
+    do_buf = torch.full((T, Hq * oh + 8), sentinel, dtype=bf, device=pa.device)
+
+    def view(buf, col0, H, hs, dim):
+        return buf[:, col0:col0 + H * hs].view(T, H, hs)[:, :, :dim]
+
+    q_v, k_v, v_v = view(fused, 0, Hq, qh, d), view(fused, wq, Hkv, kh, d), view(fused, wq + wk, Hkv, vh, e)
+    dq_v, dk_v, dv_v = view(grads, 0, Hq, qh, d), view(grads, wq, Hkv, kh, d), view(grads, wq + wk, Hkv, vh, e)
+    o_v, do_v = view(o_buf, 0, Hq, oh, e), view(do_buf, 0, Hq, oh, e)
+    q_v.copy_(dev["q"]); k_v.copy_(dev["k"]); v_v.copy_(dev["v"]); do_v.copy_(dev["do"])
+    fused_before, do_before = fused.clone(), do_buf.clone()
+
+    desc = copy.copy(pa.desc)
+    desc.q_stride_t, desc.q_stride_h = W, qh
+    desc.k_stride_t, desc.k_stride_h = W, kh
+    desc.v_stride_t, desc.v_stride_h = W, vh
+    desc.o_stride_t, desc.o_stride_h = o_buf.shape[1], oh
+    lse = torch.zeros_like(pa.lse)
+    stream = int(torch.cuda.current_stream().cuda_stream)
+    B.hbp_varlen_attn_fwd(desc, q_v, k_v, v_v, pa.cu_dev, pa.q_tiles_dev, len(pa.q_tiles), o_v, lse,
+                          pa.ws_fwd, None, stream)
+    B.hbp_varlen_attn_bwd(desc, q_v, k_v, v_v, o_v, lse, do_v, pa.cu_dev, pa.q_tiles_dev, len(pa.q_tiles),
+                          pa.kv_tiles_dev, len(pa.kv_tiles), dq_v, dk_v, dv_v, pa.ws_bwd, None, None, stream)
+    torch.cuda.synchronize()
+
+    assert torch.equal(fused, fused_before) and torch.equal(do_buf, do_before)      # inputs untouched
+    for got, ref in ((o_v, pa.o), (lse, pa.lse), (dq_v, pa.dq), (dk_v, pa.dk), (dv_v, pa.dv)):
+        assert torch.equal(got.contiguous(), ref)                                   # same as the dense layout
+    out = {"o": o_v.float().cpu().numpy(), "lse": lse.cpu().numpy(), "dq": dq_v.float().cpu().numpy(),
+           "dk": dk_v.float().cpu().numpy(), "dv": dv_v.float().cpu().numpy()}
+    compare(case, pa, out, label="strided")
+    # nothing outside the views was written
+    for buf, views in ((grads, (dq_v, dk_v, dv_v)), (o_buf, (o_v,))):
+        mask = torch.ones_like(buf, dtype=torch.bool)
+        for vw, (col0, H, hs, dim) in zip(views, ((0, Hq, qh, d), (wq, Hkv, kh, d), (wq + wk, Hkv, vh, e))
+                                          if buf is grads else ((0, Hq, oh, e),)):
+            view(mask, col0, H, hs, dim).fill_(False)
+        assert bool((buf[mask] == sentinel).all())
+
+
+def test_descriptor_rejects_strides_that_break_alignment_or_overlap_rows():
+    import copy
+    import torch
+    from paper_2503_07680_amd import binding as B
+    case = Case([40], 40, 2, 2, 64, 64, seed=32, name="bad-strides")
+    pa, dev, _ = run_gpu(case)
+    stream = int(torch.cuda.current_stream().cuda_stream)
+    for field, value in (("q_stride_h", 63), ("k_stride_t", 60), ("v_stride_h", 68), ("o_stride_t", 8)):
+        desc = copy.copy(pa.desc)
+        setattr(desc, field, value)
+        with pytest.raises(B.HbpError):
+            B.hbp_varlen_attn_fwd(desc, dev["q"], dev["k"], dev["v"], pa.cu_dev, pa.q_tiles_dev,
+                                  len(pa.q_tiles), pa.o, pa.lse, pa.ws_fwd, None, stream)
+    torch.cuda.synchronize()
