@@ -84,7 +84,9 @@ typedef struct {
   int32_t n_q_heads, n_kv_heads;
   int32_t d_qk, d_v;
   float softmax_scale;  /* <= 0: 1/sqrt(d_qk)                                          */
-  int32_t reserved;     /* must be 0                                                    */
+  int32_t fwd_tile_rows; /* rows per tile of the query-tile list given to the FORWARD: 0 = the
+                          * hbp_tile_rows value; hbp_fwd_tile_rows() says which larger size, if
+                          * any, the forward kernel of this head layout also takes           */
   /* strides in elements; 0 = dense ([T,H,dim] contiguous).  dQ/dK/dV/dO/O use the o_ and
    * the q_/k_/v_ strides of the tensor they mirror (dO and O share o_*).               */
   int64_t q_stride_t, q_stride_h, k_stride_t, k_stride_h;
@@ -95,6 +97,14 @@ typedef struct {
  * which = HBP_FWD: query tiles of the forward; HBP_BWD: key tiles of the backward.
  * Returns HBP_ERR_UNSUPPORTED for other head dims. */
 hbp_status hbp_tile_rows(int32_t d_qk, int32_t d_v, int32_t which, int32_t* rows_out);
+
+/* Preferred rows per query tile for the FORWARD of this problem (reads the head counts and dims of
+ * desc only).  With an odd number of query heads per kv head (multi-head attention included) the
+ * forward kernel shares its K/V stream between the two 128-row halves of a 256-row tile instead of
+ * between two heads of a group, so 256 is returned; otherwise the hbp_tile_rows value.  A caller
+ * that plans the forward's list with this size stores it in desc->fwd_tile_rows; the backward keeps
+ * taking a query-tile list made with hbp_tile_rows(..., HBP_FWD). */
+hbp_status hbp_fwd_tile_rows(const hbp_attn_desc* desc, int32_t* rows_out);
 
 /* Bytes of device workspace a call needs (256-byte aligned base required).
  * which = HBP_FWD or HBP_BWD.  Forward: the scheduler's per-die queue counters.  Backward: two
@@ -128,11 +138,12 @@ hbp_status hbp_profile_capacity(const hbp_attn_desc* desc, int32_t which, int32_
  * probabilities rounded to bf16 before the PV product, O stored bf16, LSE fp32.
  *
  * q,k,v,o,lse,cu_seqlens,q_tiles,workspace,profile: DEVICE.  desc: HOST.
- * q_tiles: the HBP_TILES_QUERY list of hbp_pack_plan made with hbp_tile_rows(..., HBP_FWD);
+ * q_tiles: the HBP_TILES_QUERY list of hbp_pack_plan made with hbp_tile_rows(..., HBP_FWD), or
+ * with desc->fwd_tile_rows rows when that is set;
  * items are served longest first by a persistent grid.  Tiles that are malformed (outside
  * their sample, longer than the tile size) are skipped, never dereferenced.
  * Rows of O/LSE not covered by any tile are left untouched.  n_q_tiles == 0 or T == 0: no-op.
- * Errors: INVALID_ARG (null pointers, negative counts, reserved != 0), SHAPE, UNSUPPORTED,
+ * Errors: INVALID_ARG (null pointers, negative counts, a fwd_tile_rows the layout does not take), SHAPE, UNSUPPORTED,
  * WORKSPACE, DEVICE.  Nothing is launched when an error is returned.
  */
 hbp_status hbp_varlen_attn_fwd(const hbp_attn_desc* desc, const void* q, const void* k,
@@ -153,7 +164,8 @@ hbp_status hbp_varlen_attn_fwd(const hbp_attn_desc* desc, const void* q, const v
  * registers over the query blocks and over the query heads of each kv head) and the persistent
  * query-tile kernel (dQ; it recomputes S and dP).  No atomics: every output element is written
  * once, results are bit-stable.
- * q_tiles: the HBP_TILES_QUERY list made with hbp_tile_rows(..., HBP_FWD) (the forward's list);
+ * q_tiles: the HBP_TILES_QUERY list made with hbp_tile_rows(..., HBP_FWD) (the forward's list
+ * unless that was planned with a larger desc->fwd_tile_rows, which the backward ignores);
  * kv_tiles: the HBP_TILES_KEY list made with hbp_tile_rows(..., HBP_BWD).
  * o and lse are the forward's outputs.  dK/dV rows covered by a key tile and dQ rows covered by a
  * query tile are written; others are left untouched.  profile / profile_dq: optional records of

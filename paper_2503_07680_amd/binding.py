@@ -14,7 +14,7 @@ import numpy as np
 HBP_FWD, HBP_BWD, HBP_BWD_DQ = 0, 1, 2
 HBP_TILES_QUERY, HBP_TILES_KEY = 0, 1
 
-EXPORTED_SYMBOLS = ["hbp_status_string", "hbp_pack_plan", "hbp_tile_rows", "hbp_workspace_bytes",
+EXPORTED_SYMBOLS = ["hbp_status_string", "hbp_pack_plan", "hbp_tile_rows", "hbp_fwd_tile_rows", "hbp_workspace_bytes",
                     "hbp_profile_capacity", "hbp_varlen_attn_fwd", "hbp_varlen_attn_bwd",
                     "hbp_set_kernel_events", "hbp_mfma_probe", "hbp_balance_packing",
                     "hbp_packed_ce_workspace_bytes", "hbp_packed_ce", "hbp_auto_select"]
@@ -63,7 +63,7 @@ class AttnDesc(ctypes.Structure):
     _fields_ = [("total_tokens", ctypes.c_int32), ("n_samples", ctypes.c_int32),
                 ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
                 ("d_qk", ctypes.c_int32), ("d_v", ctypes.c_int32),
-                ("softmax_scale", ctypes.c_float), ("reserved", ctypes.c_int32),
+                ("softmax_scale", ctypes.c_float), ("fwd_tile_rows", ctypes.c_int32),
                 ("q_stride_t", ctypes.c_int64), ("q_stride_h", ctypes.c_int64),
                 ("k_stride_t", ctypes.c_int64), ("k_stride_h", ctypes.c_int64),
                 ("v_stride_t", ctypes.c_int64), ("v_stride_h", ctypes.c_int64),
@@ -91,6 +91,8 @@ def load_library():
     lib.hbp_pack_plan.argtypes = [i32p, i32, i32, i32, i32, i32p, i32, i32p, i32p, vp, i64p, i32, i32p, i64p]
     lib.hbp_tile_rows.restype = i32
     lib.hbp_tile_rows.argtypes = [i32, i32, i32, i32p]
+    lib.hbp_fwd_tile_rows.restype = i32
+    lib.hbp_fwd_tile_rows.argtypes = [descp, i32p]
     lib.hbp_workspace_bytes.restype = i32
     lib.hbp_workspace_bytes.argtypes = [descp, i32, ctypes.POINTER(ctypes.c_size_t)]
     lib.hbp_profile_capacity.restype = i32
@@ -227,6 +229,15 @@ def hbp_tile_rows(d_qk: int, d_v: int, which: int) -> int:
     st = load_library().hbp_tile_rows(int(d_qk), int(d_v), int(which), ctypes.byref(out))
     if st != 0:
         raise HbpError(st, "hbp_tile_rows")
+    return int(out.value)
+
+
+def hbp_fwd_tile_rows(desc: AttnDesc) -> int:
+    """Preferred rows per query tile of the forward's list for this head layout."""
+    out = ctypes.c_int32()
+    st = load_library().hbp_fwd_tile_rows(ctypes.byref(desc), ctypes.byref(out))
+    if st != 0:
+        raise HbpError(st, "hbp_fwd_tile_rows")
     return int(out.value)
 
 

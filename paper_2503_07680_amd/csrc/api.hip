@@ -8,6 +8,7 @@ namespace {
 
 constexpr int kNumCU = 256;          // MI355X: 8 accelerator dies x 32 compute units
 constexpr size_t kCounterBytes = 2048;  // two sets of 8 per-die counters, 128 bytes apart
+constexpr int kTileRows = 128;       // rows per query / key tile of every kernel (the forward also takes 256)
 
 bool dims_supported(int d_qk, int d_v) {
   return (d_qk == 64 && d_v == 64) || (d_qk == 128 && d_v == 128) || (d_qk == 192 && d_v == 128);
@@ -20,13 +21,15 @@ struct Strides {
 
 hbp_status check_desc(const hbp_attn_desc* d, Strides* st) {
   if (!d) return HBP_ERR_INVALID_ARG;
-  if (d->reserved != 0) return HBP_ERR_INVALID_ARG;
   if (d->total_tokens < 0 || d->n_samples < 0 || d->n_q_heads <= 0 || d->n_kv_heads <= 0 ||
       d->d_qk <= 0 || d->d_v <= 0)
     return HBP_ERR_INVALID_ARG;
   if (!std::isfinite(d->softmax_scale)) return HBP_ERR_INVALID_ARG;
   if (d->n_q_heads % d->n_kv_heads) return HBP_ERR_SHAPE;
   if (!dims_supported(d->d_qk, d->d_v)) return HBP_ERR_UNSUPPORTED;
+  if (d->fwd_tile_rows != 0 && d->fwd_tile_rows != kTileRows &&
+      !(d->fwd_tile_rows == 2 * kTileRows && (d->n_q_heads / d->n_kv_heads) % 2 == 1))
+    return HBP_ERR_INVALID_ARG;
   auto fix = [](int64_t s, int64_t dense) { return s == 0 ? dense : s; };
   st->q_sh = fix(d->q_stride_h, d->d_qk);
   st->q_st = fix(d->q_stride_t, (int64_t)d->n_q_heads * d->d_qk);
@@ -202,7 +205,16 @@ extern "C" hbp_status hbp_tile_rows(int32_t d_qk, int32_t d_v, int32_t which, in
   if (!rows_out) return HBP_ERR_INVALID_ARG;
   if (which != HBP_FWD && which != HBP_BWD) return HBP_ERR_INVALID_ARG;
   if (!dims_supported(d_qk, d_v)) return HBP_ERR_UNSUPPORTED;
-  *rows_out = 128;
+  *rows_out = kTileRows;
+  return HBP_OK;
+}
+
+extern "C" hbp_status hbp_fwd_tile_rows(const hbp_attn_desc* desc, int32_t* rows_out) {
+  if (!desc || !rows_out) return HBP_ERR_INVALID_ARG;
+  if (desc->n_q_heads <= 0 || desc->n_kv_heads <= 0) return HBP_ERR_INVALID_ARG;
+  if (desc->n_q_heads % desc->n_kv_heads) return HBP_ERR_SHAPE;
+  if (!dims_supported(desc->d_qk, desc->d_v)) return HBP_ERR_UNSUPPORTED;
+  *rows_out = (desc->n_q_heads / desc->n_kv_heads) % 2 == 1 ? 2 * kTileRows : kTileRows;
   return HBP_OK;
 }
 
@@ -264,7 +276,7 @@ extern "C" hbp_status hbp_varlen_attn_fwd(const hbp_attn_desc* desc, const void*
 
   hipStream_t hs = static_cast<hipStream_t>(stream);
   if (hbp::launch_zero_counters(p.counter, hs) != 0) return HBP_ERR_DEVICE;
-  if (hbp::launch_fwd(desc->d_qk, desc->d_v, p, kNumCU, hs, g_events[HBP_FWD][0], g_events[HBP_FWD][1]) != 0) return HBP_ERR_DEVICE;
+  if (hbp::launch_fwd(desc->d_qk, desc->d_v, p, desc->fwd_tile_rows ? desc->fwd_tile_rows : kTileRows, kNumCU, hs, g_events[HBP_FWD][0], g_events[HBP_FWD][1]) != 0) return HBP_ERR_DEVICE;
   return HBP_OK;
 }
 

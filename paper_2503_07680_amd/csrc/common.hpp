@@ -420,7 +420,8 @@ constexpr int kCeMaxWorkgroups = 2048;
 // launchers implemented in the .hip files; return hipError_t as int
 // ev0/ev1: optional events recorded around the persistent main kernel
 // n_cu: compute units to fill (the kernel picks its own workgroup shape and grid)
-int launch_fwd(int d_qk, int d_v, const FwdParams& p, int n_cu, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
+int launch_fwd(int d_qk, int d_v, const FwdParams& p, int tile_rows, int n_cu, hipStream_t s, hipEvent_t ev0,
+               hipEvent_t ev1);
 // ev: {dkdv start, dkdv stop, dq start, dq stop}, entries may be null
 int launch_bwd(int d_qk, int d_v, const BwdParams& p, int grid_dq, int grid_dkdv, hipStream_t s, hipEvent_t* ev);
 int launch_zero_counters(int32_t* counters, hipStream_t s);  // the kNumXcd forward counters

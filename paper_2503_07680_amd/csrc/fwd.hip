@@ -247,14 +247,19 @@ struct FwdWave {
   }
 };
 
-// HP: query heads per workgroup.  With HP = 2 the workgroup has eight wavefronts, four per head, and
-// both heads (same kv head) work off the same K/V tiles in LDS, which halves the L2 -> LDS copy
-// traffic per MFMA; it needs an even group size.  Either way a compute unit holds eight wavefronts.
-template <int DQK, int DV, int HP>
-__global__ __launch_bounds__(kThreads * HP, 2 / HP) void fwd_kernel(const FwdParams p) {
-  constexpr int NW = 4 * HP;
+// HP: query heads per workgroup, TP: 128-row query tiles per workgroup (HP * TP <= 2).  With
+// HP = 2 the workgroup has eight wavefronts, four per head, and both heads (same kv head) work off
+// the same K/V tiles in LDS, which halves the L2 -> LDS copy traffic per MFMA; it needs an even
+// group size.  With TP = 2 the eight wavefronts take 32 rows each of a tile of up to 256 rows of one
+// head and share the K/V stream in the same way (every wavefront stops at its own diagonal): the
+// form for odd group sizes, multi-head attention included.  Either way a compute unit holds eight
+// wavefronts.
+template <int DQK, int DV, int HP, int TP>
+__global__ __launch_bounds__(kThreads * HP * TP, 2 / (HP * TP)) void fwd_kernel(const FwdParams p) {
+  static_assert(HP * TP <= 2, "eight wavefronts per compute unit");
+  constexpr int NW = 4 * HP * TP;
   using W = FwdWave<DQK, DV>;
-  constexpr int BM = 128, BN = W::BN;
+  constexpr int BM = 128 * TP, BN = W::BN;
   constexpr int KRB = W::KRB, VRB = W::VRB, K_TILE = W::K_TILE, V_TILE = W::V_TILE;
   constexpr int NC = W::NC, NEB = W::NEB;
 
@@ -264,7 +269,7 @@ __global__ __launch_bounds__(kThreads * HP, 2 / HP) void fwd_kernel(const FwdPar
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int rw = wave & 3;  // which 32 rows of the query tile
+  const int rw = wave % (4 * TP);  // which 32 rows of the query tile
   const int lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
 
   W w;
@@ -299,7 +304,7 @@ __global__ __launch_bounds__(kThreads * HP, 2 / HP) void fwd_kernel(const FwdPar
   for (;;) {
     int tile_idx, h;
     if (!next_item(wq, (int*)smem, tid, q_cur, q_tried, tile_idx, h)) break;
-    h = h * HP + (wave >> 2);  // this wave's head
+    h = h * HP + wave / (4 * TP);  // this wave's head
     uint64_t t0 = 0;
     if (p.prof && tid == 0) {
       t0 = wall_clock64();
@@ -497,33 +502,35 @@ int launch_zero_counters(int32_t* counters, hipStream_t s) {
   return (int)hipGetLastError();
 }
 
-template <int DQK, int DV, int HP>
+template <int DQK, int DV, int HP, int TP>
 static int launch_fwd_hp(const FwdParams& p, int n_cu, hipStream_t s) {
   constexpr int lds_bytes = 2 * 64 * (DQK * 2 + DV * 2);
   static bool attr_set = false;
   if (!attr_set) {
-    const hipError_t e = hipFuncSetAttribute((const void*)fwd_kernel<DQK, DV, HP>,
+    const hipError_t e = hipFuncSetAttribute((const void*)fwd_kernel<DQK, DV, HP, TP>,
                                              hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (e != hipSuccess) return (int)e;
     attr_set = true;
   }
-  const int64_t n_items = (int64_t)p.n_tiles * (p.Hq / HP), cap = (int64_t)n_cu * (2 / HP);
+  const int64_t n_items = (int64_t)p.n_tiles * (p.Hq / HP), cap = (int64_t)n_cu * (2 / (HP * TP));
   const int grid = (int)(n_items < cap ? n_items : cap);
-  hipLaunchKernelGGL((fwd_kernel<DQK, DV, HP>), dim3(grid), dim3(kThreads * HP), lds_bytes, s, p);
+  hipLaunchKernelGGL((fwd_kernel<DQK, DV, HP, TP>), dim3(grid), dim3(kThreads * HP * TP), lds_bytes, s, p);
   return (int)hipGetLastError();
 }
+// tile_rows: rows per query tile of the worklist, 128 or (odd group sizes only) 256
 template <int DQK, int DV>
-static int launch_fwd_t(const FwdParams& p, int n_cu, hipStream_t s) {
-  return p.g % 2 == 0 ? launch_fwd_hp<DQK, DV, 2>(p, n_cu, s) : launch_fwd_hp<DQK, DV, 1>(p, n_cu, s);
+static int launch_fwd_t(const FwdParams& p, int tile_rows, int n_cu, hipStream_t s) {
+  if (p.g % 2 == 0) return tile_rows == 128 ? launch_fwd_hp<DQK, DV, 2, 1>(p, n_cu, s) : (int)hipErrorInvalidValue;
+  return tile_rows == 256 ? launch_fwd_hp<DQK, DV, 1, 2>(p, n_cu, s) : launch_fwd_hp<DQK, DV, 1, 1>(p, n_cu, s);
 }
 
-int launch_fwd(int d_qk, int d_v, const FwdParams& p, int n_cu, hipStream_t s, hipEvent_t ev0,
-               hipEvent_t ev1) {
+int launch_fwd(int d_qk, int d_v, const FwdParams& p, int tile_rows, int n_cu, hipStream_t s,
+               hipEvent_t ev0, hipEvent_t ev1) {
   if (ev0 && hipEventRecord(ev0, s) != hipSuccess) return (int)hipErrorInvalidValue;
   int e;
-  if (d_qk == 64 && d_v == 64) e = launch_fwd_t<64, 64>(p, n_cu, s);
-  else if (d_qk == 128 && d_v == 128) e = launch_fwd_t<128, 128>(p, n_cu, s);
-  else if (d_qk == 192 && d_v == 128) e = launch_fwd_t<192, 128>(p, n_cu, s);
+  if (d_qk == 64 && d_v == 64) e = launch_fwd_t<64, 64>(p, tile_rows, n_cu, s);
+  else if (d_qk == 128 && d_v == 128) e = launch_fwd_t<128, 128>(p, tile_rows, n_cu, s);
+  else if (d_qk == 192 && d_v == 128) e = launch_fwd_t<192, 128>(p, tile_rows, n_cu, s);
   else return (int)hipErrorInvalidValue;
   if (e == 0 && ev1 && hipEventRecord(ev1, s) != hipSuccess) return (int)hipErrorInvalidValue;
   return e;

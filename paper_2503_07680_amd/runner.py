@@ -18,7 +18,7 @@ class PackedAttention:
 
     def __init__(self, lengths: Sequence[int], pack_len: int, n_q_heads: int, n_kv_heads: int,
                  d_qk: int, d_v: int, softmax_scale: float = 0.0, device: str = "cuda:0",
-                 with_profile: bool = False):
+                 with_profile: bool = False, fwd_tile_rows: Optional[int] = None):
         if not torch.cuda.is_available():
             raise RuntimeError("PackedAttention needs a GPU: there is no CPU fallback")
         B.load_library()
@@ -27,6 +27,15 @@ class PackedAttention:
         self.rows_bwd = B.hbp_tile_rows(d_qk, d_v, B.HBP_BWD)
         self.cu, self.n_consumed, self.q_tiles, self.q_cost, self.pack_cost = B.hbp_pack_plan(
             lengths, pack_len, self.rows_fwd, B.HBP_TILES_QUERY)
+        # the forward's own list when the head layout prefers larger query tiles (odd group sizes)
+        self.rows_fwd_pref = B.hbp_fwd_tile_rows(B.AttnDesc(n_q_heads=n_q_heads, n_kv_heads=n_kv_heads,
+                                                            d_qk=d_qk, d_v=d_v))
+        self.fwd_tiles, self.fwd_cost = self.q_tiles, self.q_cost
+        if fwd_tile_rows is None:
+            fwd_tile_rows = self.rows_fwd_pref
+        if fwd_tile_rows != self.rows_fwd:
+            _, _, self.fwd_tiles, self.fwd_cost, _ = B.hbp_pack_plan(lengths, pack_len, fwd_tile_rows,
+                                                                     B.HBP_TILES_QUERY)
         _, _, self.kv_tiles, self.kv_cost, _ = B.hbp_pack_plan(
             lengths, pack_len, self.rows_bwd, B.HBP_TILES_KEY)
         self.T = int(self.cu[-1])
@@ -34,10 +43,13 @@ class PackedAttention:
         self.Hq, self.Hkv, self.d_qk, self.d_v = n_q_heads, n_kv_heads, d_qk, d_v
         self.desc = B.AttnDesc(total_tokens=self.T, n_samples=self.n_samples, n_q_heads=n_q_heads,
                                n_kv_heads=n_kv_heads, d_qk=d_qk, d_v=d_v,
-                               softmax_scale=float(softmax_scale))
+                               softmax_scale=float(softmax_scale),
+                               fwd_tile_rows=0 if fwd_tile_rows == self.rows_fwd else int(fwd_tile_rows))
         dev = self.device
         self.cu_dev = torch.from_numpy(self.cu).to(dev)
         self.q_tiles_dev = torch.from_numpy(self.q_tiles).to(dev)
+        self.fwd_tiles_dev = (self.q_tiles_dev if self.fwd_tiles is self.q_tiles
+                              else torch.from_numpy(self.fwd_tiles).to(dev))
         self.kv_tiles_dev = torch.from_numpy(self.kv_tiles).to(dev)
         self.ws_fwd = torch.empty(B.hbp_workspace_bytes(self.desc, B.HBP_FWD), dtype=torch.uint8, device=dev)
         self.ws_bwd = None
@@ -66,7 +78,7 @@ class PackedAttention:
         return int(torch.cuda.current_stream(self.device).cuda_stream)
 
     def forward(self, q, k, v, profile: bool = False):
-        B.hbp_varlen_attn_fwd(self.desc, q, k, v, self.cu_dev, self.q_tiles_dev, len(self.q_tiles),
+        B.hbp_varlen_attn_fwd(self.desc, q, k, v, self.cu_dev, self.fwd_tiles_dev, len(self.fwd_tiles),
                               self.o, self.lse, self.ws_fwd, self.prof_fwd if profile else None,
                               self._stream())
         return self.o, self.lse

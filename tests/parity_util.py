@@ -56,6 +56,10 @@ def check_plan(case: Case, pa):
         ocu, onc, otiles, ocost, opc = oracle.pack_plan(case.lengths, case.pack_len, rows, kind)
         assert pa.cu.tolist() == ocu and pa.n_consumed == onc and pa.pack_cost == opc
         assert [tuple(t) for t in tiles.tolist()] == otiles and cost.tolist() == ocost
+    if pa.fwd_tiles is not pa.q_tiles:      # the forward's own list (larger query tiles)
+        rows = pa.desc.fwd_tile_rows
+        _, _, otiles, ocost, _ = oracle.pack_plan(case.lengths, case.pack_len, rows, 0)
+        assert [tuple(t) for t in pa.fwd_tiles.tolist()] == otiles and pa.fwd_cost.tolist() == ocost
 
 
 def compare(case: Case, pa, out, q_heads=None, rows=None, cols=None, label=""):

@@ -44,6 +44,11 @@ def test_tile_rows_and_workspace_queries():
         H.hbp_tile_rows(96, 96, H.HBP_FWD)
     assert e.value.status == 3
     d = desc()
+    assert H.hbp_fwd_tile_rows(d) == H.hbp_tile_rows(128, 128, H.HBP_FWD)           # even group: one size
+    mha = desc(n_q_heads=4, n_kv_heads=4)
+    assert H.hbp_fwd_tile_rows(mha) == 2 * H.hbp_tile_rows(128, 128, H.HBP_FWD)     # odd group: 256 rows
+    mha.fwd_tile_rows = H.hbp_fwd_tile_rows(mha)
+    assert H.hbp_workspace_bytes(mha, H.HBP_FWD) >= 4                               # and the descriptor takes it
     assert H.hbp_workspace_bytes(d, H.HBP_FWD) >= 4
     need = H.hbp_workspace_bytes(d, H.HBP_BWD)
     assert need >= 256 * 4 * 4
@@ -55,7 +60,8 @@ def test_tile_rows_and_workspace_queries():
     (dict(d_qk=96, d_v=96), 3),                 # unsupported dims
     (dict(total_tokens=-1), 1),
     (dict(n_q_heads=0), 1),
-    (dict(reserved=7), 1),
+    (dict(fwd_tile_rows=7), 1),                 # not a tile size the forward takes
+    (dict(fwd_tile_rows=256), 1),               # 256-row tiles need an odd group size (here 2)
     (dict(q_stride_h=64), 2),                   # head stride smaller than the head
     (dict(k_stride_t=100), 2),                  # not a multiple of 8 elements
 ])

@@ -133,7 +133,7 @@ def test_strided_views_of_fused_buffers(Hq, Hkv, d, e, pad_h):
     desc.o_stride_t, desc.o_stride_h = o_buf.shape[1], oh
     lse = torch.zeros_like(pa.lse)
     stream = int(torch.cuda.current_stream().cuda_stream)
-    B.hbp_varlen_attn_fwd(desc, q_v, k_v, v_v, pa.cu_dev, pa.q_tiles_dev, len(pa.q_tiles), o_v, lse,
+    B.hbp_varlen_attn_fwd(desc, q_v, k_v, v_v, pa.cu_dev, pa.fwd_tiles_dev, len(pa.fwd_tiles), o_v, lse,
                           pa.ws_fwd, None, stream)
     B.hbp_varlen_attn_bwd(desc, q_v, k_v, v_v, o_v, lse, do_v, pa.cu_dev, pa.q_tiles_dev, len(pa.q_tiles),
                           pa.kv_tiles_dev, len(pa.kv_tiles), dq_v, dk_v, dv_v, pa.ws_bwd, None, None, stream)
@@ -165,6 +165,26 @@ def test_descriptor_rejects_strides_that_break_alignment_or_overlap_rows():
         desc = copy.copy(pa.desc)
         setattr(desc, field, value)
         with pytest.raises(B.HbpError):
-            B.hbp_varlen_attn_fwd(desc, dev["q"], dev["k"], dev["v"], pa.cu_dev, pa.q_tiles_dev,
-                                  len(pa.q_tiles), pa.o, pa.lse, pa.ws_fwd, None, stream)
+            B.hbp_varlen_attn_fwd(desc, dev["q"], dev["k"], dev["v"], pa.cu_dev, pa.fwd_tiles_dev,
+                                  len(pa.fwd_tiles), pa.o, pa.lse, pa.ws_fwd, None, stream)
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("Hq,Hkv,d,e", [(3, 3, 128, 128), (3, 1, 64, 64), (2, 2, 192, 128)])
+def test_odd_group_sizes_take_256_row_query_tiles_in_the_forward(Hq, Hkv, d, e):
+    """With an odd number of query heads per kv head the forward pairs the two halves of a 256-row
+    tile instead of two heads.  Both tile sizes must meet the oracle's bars and agree bit for bit
+    (a row's arithmetic does not depend on which wavefronts share its K/V stream)."""
+    import torch
+    from paper_2503_07680_amd.runner import PackedAttention
+    lengths = [700, 129, 256, 257, 31, 1, 400]
+    case = Case(lengths, sum(lengths), Hq, Hkv, d, e, seed=33, name="tile256-%d-%d-%d" % (Hq, Hkv, d))
+    pa, dev, out = run_gpu(case)
+    assert pa.rows_fwd_pref == 256 and pa.desc.fwd_tile_rows == 256 and len(pa.fwd_tiles) < len(pa.q_tiles)
+    check_plan(case, pa)
+    compare(case, pa, out)
+    small = PackedAttention(case.lengths, case.pack_len, Hq, Hkv, d, e, case.scale, fwd_tile_rows=128)
+    assert small.desc.fwd_tile_rows == 0
+    small.forward(dev["q"], dev["k"], dev["v"])
+    torch.cuda.synchronize()
+    assert torch.equal(small.o, pa.o) and torch.equal(small.lse, pa.lse)
