@@ -189,6 +189,31 @@ def packed_ce_timing(ev, stream, T=8192, V=128256, n_samples=12, reps=10):
             "loss": float(loss.item())}
 
 
+def plan_timing(w, pa):
+    """Host planning of this pack (both worklists through hbp_pack_plan) and the upload of
+    cu_seqlens and the worklists: outside the timed region, reported on their own."""
+    import torch
+    import paper_2503_07680_amd as H
+    reps, per_call = 20, []
+    for i in range(reps + 3):
+        t0 = time.perf_counter()
+        H.hbp_pack_plan(w.lengths, w.pack_len, pa.rows_fwd, H.HBP_TILES_QUERY)
+        H.hbp_pack_plan(w.lengths, w.pack_len, pa.rows_bwd, H.HBP_TILES_KEY)
+        if i >= 3:
+            per_call.append((time.perf_counter() - t0) * 1e3)
+    plan_ms = float(np.median(per_call))
+    host = [torch.from_numpy(a).pin_memory() for a in (pa.cu, pa.q_tiles, pa.kv_tiles)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        devs = [h.to(pa.device, non_blocking=True) for h in host]
+    torch.cuda.synchronize()
+    h2d_ms = (time.perf_counter() - t0) * 1e3 / reps
+    return {"pack_plan_host_ms": plan_ms, "worklist_h2d_ms": h2d_ms,
+            "n_query_tiles": int(len(pa.q_tiles)), "n_key_tiles": int(len(pa.kv_tiles)),
+            "bytes_uploaded": int(sum(h.numel() * h.element_size() for h in host))}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -322,6 +347,7 @@ def main():
                      "traffic": DKDV_TRAFFIC_BYTES.get(args.config) if args.seed == 0 else None},
         "busy_time_spread": {"fwd": spread_f, "bwd_dkdv": spread_b, "bwd_dq": spread_q},
     }
+    out["plan"] = plan_timing(w, pa)
     out["balance_packing"] = planner_timing()
     out["auto_selection"] = auto_select_timing()
     del dev
