@@ -143,7 +143,8 @@ hbp_status hbp_profile_capacity(const hbp_attn_desc* desc, int32_t which, int32_
  * items are served longest first by a persistent grid.  Tiles that are malformed (outside
  * their sample, longer than the tile size) are skipped, never dereferenced.
  * Rows of O/LSE not covered by any tile are left untouched.  n_q_tiles == 0 or T == 0: no-op.
- * Errors: INVALID_ARG (null pointers, negative counts, a fwd_tile_rows the layout does not take), SHAPE, UNSUPPORTED,
+ * Errors: INVALID_ARG (null pointers, negative counts, n_q_tiles * n_q_heads above INT32_MAX, a
+ * fwd_tile_rows the layout does not take), SHAPE, UNSUPPORTED,
  * WORKSPACE, DEVICE.  Nothing is launched when an error is returned.
  */
 hbp_status hbp_varlen_attn_fwd(const hbp_attn_desc* desc, const void* q, const void* k,

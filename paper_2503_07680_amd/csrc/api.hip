@@ -1,4 +1,5 @@
 // C ABI: argument validation on the host, then kernel launches on the caller's stream.
+#include <climits>
 #include <cmath>
 #include <cstring>
 
@@ -72,6 +73,9 @@ float resolve_scale(const hbp_attn_desc* d) {
 }
 
 hipEvent_t g_events[4][2] = {{nullptr, nullptr}, {nullptr, nullptr}, {nullptr, nullptr}, {nullptr, nullptr}};
+
+// the schedulers count (tile, head) items in 32-bit integers
+bool item_count_fits(int32_t n_tiles, int32_t n_heads) { return (int64_t)n_tiles * n_heads <= INT32_MAX; }
 
 int grid_for(int64_t n_items, int blocks_per_cu) {
   const int64_t cap = (int64_t)kNumCU * blocks_per_cu;
@@ -246,7 +250,7 @@ extern "C" hbp_status hbp_varlen_attn_fwd(const hbp_attn_desc* desc, const void*
   Strides st;
   const hbp_status s = check_desc(desc, &st);
   if (s != HBP_OK) return s;
-  if (n_q_tiles < 0) return HBP_ERR_INVALID_ARG;
+  if (n_q_tiles < 0 || !item_count_fits(n_q_tiles, desc->n_q_heads)) return HBP_ERR_INVALID_ARG;
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < kCounterBytes)
     return HBP_ERR_WORKSPACE;
   if (desc->total_tokens == 0 || n_q_tiles == 0) return HBP_OK;
@@ -292,6 +296,8 @@ extern "C" hbp_status hbp_varlen_attn_bwd(const hbp_attn_desc* desc, const void*
   const hbp_status s = check_desc(desc, &st);
   if (s != HBP_OK) return s;
   if (n_kv_tiles < 0 || n_q_tiles < 0) return HBP_ERR_INVALID_ARG;
+  if (!item_count_fits(n_q_tiles, desc->n_q_heads) || !item_count_fits(n_kv_tiles, desc->n_q_heads))
+    return HBP_ERR_INVALID_ARG;
   const BwdLayout lay = bwd_layout(desc);
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < lay.total)
     return HBP_ERR_WORKSPACE;

@@ -93,6 +93,8 @@ def test_launch_entry_points_reject_bad_arguments_before_touching_the_device():
                                    fake, fake, fake, fake, big, None, None, None) == 1
     assert lib.hbp_varlen_attn_bwd(ctypes.byref(d), fake, fake, fake, fake, fake, fake, fake, None, 1, fake, 1,
                                    fake, fake, fake, fake, big, None, None, None) == 1
+    # more (tile, head) items than the schedulers' 32-bit counters hold
+    assert lib.hbp_varlen_attn_fwd(ctypes.byref(d), fake, fake, fake, fake, fake, 2 ** 30, fake, fake, fake, wsf, None, None) == 1
     # empty problems are no-ops that launch nothing
     d0 = desc(total_tokens=0, n_samples=0)
     assert lib.hbp_varlen_attn_fwd(ctypes.byref(d0), None, None, None, None, None, 0, None, None, fake, wsf, None, None) == 0
