@@ -37,7 +37,8 @@ enum {
   HBP_ERR_UNSUPPORTED = 3, /* head dims outside the supported set                        */
   HBP_ERR_CAPACITY = 4,    /* an output array of the planner is too small                */
   HBP_ERR_WORKSPACE = 5,   /* workspace missing, misaligned or smaller than required     */
-  HBP_ERR_DEVICE = 6       /* the HIP runtime refused the launch (hipGetLastError)       */
+  HBP_ERR_DEVICE = 6,      /* the HIP runtime refused the launch (hipGetLastError)       */
+  HBP_ERR_NO_MEMORY = 7    /* a host planner could not allocate its working memory       */
 };
 
 /* Static, never-freed description of a status code. */

@@ -93,6 +93,7 @@ extern "C" const char* hbp_status_string(hbp_status s) {
     case HBP_ERR_CAPACITY: return "output array too small";
     case HBP_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case HBP_ERR_DEVICE: return "HIP runtime error at launch";
+    case HBP_ERR_NO_MEMORY: return "out of host memory";
     default: return "unknown status";
   }
 }

@@ -4,6 +4,7 @@
 #include <cmath>
 #include <cstdint>
 #include <limits>
+#include <new>
 
 #include "hbp.h"
 
@@ -40,7 +41,7 @@ hbp_strategy find_best_sp_ckpt(const hbp_profile& pr, int32_t l, const int32_t* 
 
 }  // namespace
 
-extern "C" hbp_status hbp_auto_select(const int32_t* lengths, int32_t n_lengths, const int32_t* sp_set,
+static hbp_status hbp_auto_select_impl(const int32_t* lengths, int32_t n_lengths, const int32_t* sp_set,
                                       int32_t n_sp, int32_t c_min, int32_t c_max, const hbp_profile* profile,
                                       hbp_strategy* per_length_or_null, hbp_group* groups,
                                       int32_t* n_groups_out, int32_t* best_index_out_or_null) {
@@ -82,4 +83,19 @@ extern "C" hbp_status hbp_auto_select(const int32_t* lengths, int32_t n_lengths,
   *n_groups_out = m;
   if (best_index_out_or_null) *best_index_out_or_null = j;
   return HBP_OK;
+}
+
+// The planner allocates host memory: running out of it is reported, never thrown across the C boundary.
+extern "C" hbp_status hbp_auto_select(const int32_t* lengths, int32_t n_lengths, const int32_t* sp_set,
+                                      int32_t n_sp, int32_t c_min, int32_t c_max, const hbp_profile* profile,
+                                      hbp_strategy* per_length_or_null, hbp_group* groups,
+                                      int32_t* n_groups_out, int32_t* best_index_out_or_null) {
+  try {
+    return hbp_auto_select_impl(lengths, n_lengths, sp_set, n_sp, c_min, c_max, profile, per_length_or_null, groups,
+                                n_groups_out, best_index_out_or_null);
+  } catch (const std::bad_alloc&) {
+    return HBP_ERR_NO_MEMORY;
+  } catch (...) {
+    return HBP_ERR_INVALID_ARG;
+  }
 }

@@ -13,6 +13,7 @@
 #include <algorithm>
 #include <cstdint>
 #include <limits>
+#include <new>
 #include <vector>
 
 namespace {
@@ -84,7 +85,7 @@ double ratio_to_max(const std::vector<int64_t>& v) {
 
 }  // namespace
 
-extern "C" hbp_status hbp_balance_packing(const int32_t* lengths, int32_t n_samples,
+static hbp_status hbp_balance_packing_impl(const int32_t* lengths, int32_t n_samples,
                                           const int32_t* group_lens, const int32_t* packs_per_batch,
                                           const int32_t* level_sp, int32_t n_levels,
                                           uint64_t shuffle_seed, int32_t* pack_items, int32_t item_cap,
@@ -221,4 +222,23 @@ extern "C" hbp_status hbp_balance_packing(const int32_t* lengths, int32_t n_samp
     metrics_or_null->ave_t = devices ? (double)t_all / (double)devices : 0.0;
   }
   return HBP_OK;
+}
+
+// The planner allocates host memory: running out of it is reported, never thrown across the C boundary.
+extern "C" hbp_status hbp_balance_packing(const int32_t* lengths, int32_t n_samples,
+                                          const int32_t* group_lens, const int32_t* packs_per_batch,
+                                          const int32_t* level_sp, int32_t n_levels,
+                                          uint64_t shuffle_seed, int32_t* pack_items, int32_t item_cap,
+                                          hbp_pack* packs, int32_t pack_cap, int32_t* n_packs_out,
+                                          hbp_batch* batches, int32_t batch_cap, int32_t* n_batches_out,
+                                          hbp_pack_metrics* metrics_or_null) {
+  try {
+    return hbp_balance_packing_impl(lengths, n_samples, group_lens, packs_per_batch, level_sp, n_levels, shuffle_seed,
+                                    pack_items, item_cap, packs, pack_cap, n_packs_out, batches, batch_cap,
+                                    n_batches_out, metrics_or_null);
+  } catch (const std::bad_alloc&) {
+    return HBP_ERR_NO_MEMORY;
+  } catch (...) {
+    return HBP_ERR_INVALID_ARG;
+  }
 }

@@ -5,6 +5,7 @@
 
 #include <algorithm>
 #include <numeric>
+#include <new>
 #include <vector>
 
 namespace {
@@ -26,7 +27,7 @@ inline int64_t key_tile_pairs(int64_t lo, int64_t hi, int64_t s) {
 
 }  // namespace
 
-extern "C" hbp_status hbp_pack_plan(const int32_t* lengths, int32_t n_lengths, int32_t pack_len,
+static hbp_status hbp_pack_plan_impl(const int32_t* lengths, int32_t n_lengths, int32_t pack_len,
                                     int32_t tile_rows, int32_t kind, int32_t* cu_seqlens,
                                     int32_t cu_cap, int32_t* n_samples_out,
                                     int32_t* n_consumed_out, hbp_tile* tiles, int64_t* tile_cost,
@@ -100,4 +101,21 @@ extern "C" hbp_status hbp_pack_plan(const int32_t* lengths, int32_t n_lengths, i
     }
   }
   return st;
+}
+
+// The planner allocates host memory: running out of it is reported, never thrown across the C boundary.
+extern "C" hbp_status hbp_pack_plan(const int32_t* lengths, int32_t n_lengths, int32_t pack_len,
+                                    int32_t tile_rows, int32_t kind, int32_t* cu_seqlens,
+                                    int32_t cu_cap, int32_t* n_samples_out,
+                                    int32_t* n_consumed_out, hbp_tile* tiles, int64_t* tile_cost,
+                                    int32_t tile_cap, int32_t* n_tiles_out,
+                                    int64_t* pack_cost_out) {
+  try {
+    return hbp_pack_plan_impl(lengths, n_lengths, pack_len, tile_rows, kind, cu_seqlens, cu_cap, n_samples_out, n_consumed_out,
+                              tiles, tile_cost, tile_cap, n_tiles_out, pack_cost_out);
+  } catch (const std::bad_alloc&) {
+    return HBP_ERR_NO_MEMORY;
+  } catch (...) {
+    return HBP_ERR_INVALID_ARG;
+  }
 }

@@ -28,6 +28,7 @@ def test_every_declared_symbol_is_exported():
 def test_status_strings():
     assert H.hbp_status_string(0) == "ok"
     assert "unsupported" in H.hbp_status_string(3)
+    assert "memory" in H.hbp_status_string(7)
     assert H.hbp_status_string(99) == "unknown status"
 
 
