@@ -222,6 +222,9 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="workload 1..5 (default 3: the mixed 32K pack)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the same steps replayed from one captured HIP graph (reported as "
+                         "graph_replay; `value` stays the eager figure)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 256 MiB device-to-device copy (known size) to scale rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters")
@@ -283,6 +286,28 @@ def main():
     fwd_k = np.array([ev.elapsed_ms(a, b) for a, b in f_ev])
     bwd_k = np.array([ev.elapsed_ms(a, b) for a, b in b_ev])
     dq_k = np.array([ev.elapsed_ms(a, b) for a, b in q_ev])
+
+    graph_info = None
+    if args.graph:
+        # the same step recorded once and replayed K times: what is left of the launch overhead
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            step()
+        for _ in range(args.warmup):
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(K):
+            g.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) * 1e3 / K
+        graph_info = {"ms_per_step": graph_ms,
+                      "useful_tflops": (fwd_flops + bwd_flops) / (graph_ms * 1e-3) / 1e12}
 
     # one extra, untimed, profiled step: per-CU busy time
     pa.forward(dev["q"], dev["k"], dev["v"], profile=True)
@@ -347,6 +372,8 @@ def main():
                      "traffic": DKDV_TRAFFIC_BYTES.get(args.config) if args.seed == 0 else None},
         "busy_time_spread": {"fwd": spread_f, "bwd_dkdv": spread_b, "bwd_dq": spread_q},
     }
+    if graph_info:
+        out["graph_replay"] = graph_info
     out["plan"] = plan_timing(w, pa)
     out["balance_packing"] = planner_timing()
     out["auto_selection"] = auto_select_timing()
