@@ -1,8 +1,9 @@
 // Forward kernel: causal attention inside each sample of a packed buffer, gfx950.
 //
-// One work item = (query tile of <=128 rows, query head).  A persistent grid takes items from
-// per-die queues in worklist order (longest causal cost first).  Per item the workgroup
-// (4 wavefronts, 32 query rows each) walks the sample's keys from the sample start to the diagonal.
+// One work item = (query tile, one or two query heads of a kv head).  A persistent grid takes items
+// from per-die queues in worklist order (longest causal cost first).  Per item the workgroup (eight
+// wavefronts of 32 query rows each: two heads x 128 rows, or one head x 256 rows; four for one head x
+// 128 rows) walks the sample's keys from the sample start to the diagonal.
 //
 //   S^T = K Q^T      K tile from LDS (A operand), Q fragments held in registers (B operand);
 //                    the accumulator then has one query per lane column, its keys in-lane, so
