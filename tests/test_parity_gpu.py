@@ -188,3 +188,35 @@ def test_odd_group_sizes_take_256_row_query_tiles_in_the_forward(Hq, Hkv, d, e):
     small.forward(dev["q"], dev["k"], dev["v"])
     torch.cuda.synchronize()
     assert torch.equal(small.o, pa.o) and torch.equal(small.lse, pa.lse)
+
+
+def test_seeded_sweep_of_random_packs():
+    """Two dozen seeded random packs: sample counts, lengths (many tiny, some spanning several tiles,
+    lengths at and around the tile edges), head layouts (odd and even groups), all three head sizes,
+    truncating and under-full pack lengths.  Every output against the oracle, plus the plan.  (Values stay
+    at the workloads' scale, sigma <= 1: the absolute bar on O is about bf16 outputs of that magnitude.)"""
+    rng = np.random.default_rng(2024)
+    dims = [(64, 64), (128, 128), (192, 128)]
+    edges = [1, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, 383, 384, 385]
+    for i in range(24):
+        n = int(rng.integers(1, 13))
+        lengths = []
+        for _ in range(n):
+            kind = rng.random()
+            if kind < 0.35:
+                lengths.append(int(rng.integers(1, 40)))
+            elif kind < 0.6:
+                lengths.append(int(rng.choice(edges)))
+            else:
+                lengths.append(int(rng.integers(40, 700)))
+        total = sum(lengths)
+        pack_len = total if i % 3 else max(1, total - int(rng.integers(0, min(total, 200))))   # sometimes truncating
+        if i % 5 == 0:
+            pack_len = total + 77                                                              # under-full
+        Hkv = int(rng.integers(1, 4))
+        g = int(rng.integers(1, 5))
+        d, e = dims[i % 3]
+        scale = 0.0 if i % 4 else float(rng.uniform(0.05, 0.3))
+        print("sweep case", i, lengths, pack_len, Hkv * g, Hkv, d, e, scale, flush=True)
+        full(Case(lengths, pack_len, Hkv * g, Hkv, d, e, seed=100 + i, sigma=float(rng.choice([0.5, 1.0])),
+                  scale=scale, name="sweep-%d" % i))
