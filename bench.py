@@ -25,8 +25,8 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA (published)
 
 # HBM bytes of one launch of the dominant kernel (backward key-tile kernel) on workload 3, from the two
 # rocprofv3 counter runs summarised in profiles/hbm_traffic_mixed32k.md:
-# FETCH_SIZE 3 317 232 KiB x 2.0 (calibration factor) + WRITE_SIZE 131 623 KiB x 1.0.
-DKDV_TRAFFIC_BYTES = {3: int((3317232 * 2.0 + 131623 * 1.0) * 1024)}
+# FETCH_SIZE 1 540 810 KiB x 2.0 (calibration factor) + WRITE_SIZE 131 623 KiB x 1.0.
+DKDV_TRAFFIC_BYTES = {3: int((1540810 * 2.0 + 131623 * 1.0) * 1024)}
 
 
 class HipEvents:

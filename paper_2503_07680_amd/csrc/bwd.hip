@@ -420,16 +420,31 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
       // block the g query heads of the group.  Every key tile of a sample needs a suffix of the same
       // blocks, so the workgroups of a die (they work on tiles of the same kv head) ask for the same
       // block at about the same time and it comes from that die's L2 once, not from HBM once per tile.
+      // That only works while they walk in step: 32 workgroups two blocks apart put 8 MB between two
+      // uses of a block, more than the L2 holds.  The w workgroups that share a kv head take the tiles
+      // of a long sample w at a time, longest first.  Tiles 0..w-1 start together and end BN/BQ blocks
+      // apart (each is that much shorter than the one before); their workgroups then take tiles
+      // w..2w-1 one after the other, BN/BQ blocks apart.  Such a tile starts as many blocks below the top
+      // as it starts late (where the first of its round is by then) and does the blocks it skipped at
+      // the end; that round ends together, the next one starts together, and so on in turns.  The
+      // order is a function of the tile number alone, so the results do not depend on timing.
+      // (With fewer than 8 workgroups per kv head there is little to share and the plain order is kept.)
+      const int w_share = (int)gridDim.x / p.Hkv;
+      int skip = w_share >= 8 && ((tl.tile / w_share) & 1) ? (tl.tile % w_share) * (BN / BQ) : 0;
+      skip = max(0, min(skip, nqb - 1));
+      const int first_blk = nqb - 1 - skip;
+      // block of the sb-th group of g steps: first_blk .. 0, then nqb-1 .. first_blk+1
+      auto block_of = [&](int sb) { return sb <= first_blk ? first_blk - sb : nqb + first_blk - sb; };
       // Copies are issued in step order; the source pointers of the next block to copy are carried
       // along instead of being recomputed from the step number.
-      const int64_t last_row = (int64_t)s0 + qb_start + (int64_t)(nqb - 1) * BQ;
-      const uint16_t* q_blk = p.q + last_row * p.q_st + (int64_t)(kh * p.g) * p.q_sh;
-      const uint16_t* o_blk = p.d_o + last_row * p.o_st + (int64_t)(kh * p.g) * p.o_sh;
-      const float* row_blk = (wave == 0 ? p.lse2 : p.D) + (int64_t)(kh * p.g) * p.T + last_row;
+      const int64_t first_row = (int64_t)s0 + qb_start + (int64_t)first_blk * BQ;
+      const uint16_t* q_blk = p.q + first_row * p.q_st + (int64_t)(kh * p.g) * p.q_sh;
+      const uint16_t* o_blk = p.d_o + first_row * p.o_st + (int64_t)(kh * p.g) * p.o_sh;
+      const float* row_blk = (wave == 0 ? p.lse2 : p.D) + (int64_t)(kh * p.g) * p.T + first_row;
       const uint16_t* q_src = q_blk;
       const uint16_t* o_src = o_blk;
       const float* row_src = row_blk;
-      int blk_next = nqb - 1, head_next = 0;
+      int blk_next = first_blk, head_next = 0;
       auto issue_next = [&](int buf) {
         const int valid = s_len - qb_start - blk_next * BQ;  // >= 1; < BQ only for the sample's last block
         q_loader.issue(q_src, q_stride_b, valid, q_lds + buf * Q_TILE, wave, lane);
@@ -441,12 +456,13 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
           const float* dst = (wave == 0 ? lse_lds : d_lds) + buf * BQ;
           async_copy4(row_src, (uint32_t)row * 4u, lds_address(dst));
         }
-        if (++head_next == p.g) {  // on to the block before
+        if (++head_next == p.g) {  // on to the block before; from the tile's own block to the sample's last
           head_next = 0;
-          --blk_next;
-          q_blk -= (int64_t)BQ * p.q_st;
-          o_blk -= (int64_t)BQ * p.o_st;
-          row_blk -= BQ;
+          const int64_t jump = blk_next == 0 ? (int64_t)(nqb - 1) * BQ : -(int64_t)BQ;
+          blk_next = blk_next == 0 ? nqb - 1 : blk_next - 1;
+          q_blk += jump * p.q_st;
+          o_blk += jump * p.o_st;
+          row_blk += jump;
           q_src = q_blk;
           o_src = o_blk;
           row_src = row_blk;
@@ -495,7 +511,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
         // the step's buffer is a compile-time constant: it goes into the immediate offset of every LDS
         // read (two copies of the step's code instead of 34 address updates per step)
         constexpr int BUF = decltype(buf_tag)::value;
-        const int qb = qb_start + (nqb - 1 - step / p.g) * BQ;
+        const int qb = qb_start + block_of(step / p.g) * BQ;
         auto sd_load = [&](int sub) {
           return [&, sub](int i) {
             Frag a;
