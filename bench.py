@@ -222,6 +222,9 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="workload 1..5 (default 3: the mixed 32K pack)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--row-pad", type=int, default=0,
+                    help="extra elements (multiple of 8) at the end of every token row of Q, K, V, O and the "
+                         "gradients (strides in the descriptor); default 0 = dense [T, H, dim]")
     ap.add_argument("--graph", action="store_true",
                     help="also time the same steps replayed from one captured HIP graph (reported as "
                          "graph_replay; `value` stays the eager figure)")
@@ -244,7 +247,8 @@ def main():
         sys.exit(1)
     H.load_library()
     w = wl.workload(args.config, args.seed)
-    pa = PackedAttention(w.lengths, w.pack_len, w.n_q_heads, w.n_kv_heads, w.d_qk, w.d_v, with_profile=True)
+    pa = PackedAttention(w.lengths, w.pack_len, w.n_q_heads, w.n_kv_heads, w.d_qk, w.d_v, with_profile=True,
+                         row_pad=args.row_pad)
     T = pa.T
     dev = {t: pa.to_device_bf16(wl.workload_tensor_bits(w, t, T)) for t in ("q", "k", "v", "do")}
     lens = np.diff(pa.cu).astype(np.int64)
@@ -353,7 +357,7 @@ def main():
         "config": {"workload": "config %d: %s (%s)" % (args.config, w.name, w.note), "seed": args.seed,
                    "total_tokens": T, "n_samples": pa.n_samples, "n_q_heads": w.n_q_heads,
                    "n_kv_heads": w.n_kv_heads, "d_qk": w.d_qk, "d_v": w.d_v, "causal_pairs": pairs,
-                   "pack_cost_sum_s2": pa.pack_cost, "useful_tflop_fwd": fwd_flops / 1e12,
+                   "pack_cost_sum_s2": pa.pack_cost, "row_pad": args.row_pad, "useful_tflop_fwd": fwd_flops / 1e12,
                    "useful_tflop_bwd": bwd_flops / 1e12},
         "useful_tflops_4gemm_bwd": (fwd_flops + dkdv_flops) / (ms_per_step * 1e-3) / 1e12,
         "kernels": {"fwd_ms_avg": float(fwd_k.mean()), "fwd_ms_min": float(fwd_k.min()),

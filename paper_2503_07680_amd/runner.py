@@ -18,7 +18,7 @@ class PackedAttention:
 
     def __init__(self, lengths: Sequence[int], pack_len: int, n_q_heads: int, n_kv_heads: int,
                  d_qk: int, d_v: int, softmax_scale: float = 0.0, device: str = "cuda:0",
-                 with_profile: bool = False, fwd_tile_rows: Optional[int] = None):
+                 with_profile: bool = False, fwd_tile_rows: Optional[int] = None, row_pad: int = 0):
         if not torch.cuda.is_available():
             raise RuntimeError("PackedAttention needs a GPU: there is no CPU fallback")
         B.load_library()
@@ -45,6 +45,14 @@ class PackedAttention:
                                n_kv_heads=n_kv_heads, d_qk=d_qk, d_v=d_v,
                                softmax_scale=float(softmax_scale),
                                fwd_tile_rows=0 if fwd_tile_rows == self.rows_fwd else int(fwd_tile_rows))
+        # row_pad: extra elements (a multiple of 8) at the end of every token row of every tensor, so that
+        # the row stride is not a power of two; 0 = dense [T, H, dim]
+        self.row_pad = int(row_pad)
+        if self.row_pad:
+            self.desc.q_stride_t = n_q_heads * d_qk + self.row_pad
+            self.desc.k_stride_t = n_kv_heads * d_qk + self.row_pad
+            self.desc.v_stride_t = n_kv_heads * d_v + self.row_pad
+            self.desc.o_stride_t = n_q_heads * d_v + self.row_pad
         dev = self.device
         self.cu_dev = torch.from_numpy(self.cu).to(dev)
         self.q_tiles_dev = torch.from_numpy(self.q_tiles).to(dev)
@@ -63,15 +71,28 @@ class PackedAttention:
             self.prof_dq = torch.zeros(n * B.PROFILE_DTYPE.itemsize, dtype=torch.uint8, device=dev)
         T = max(self.T, 1)
         bf = torch.bfloat16
-        self.o = torch.zeros((T, n_q_heads, d_v), dtype=bf, device=dev)
+        self.o = self.buffer(n_q_heads, d_v)
         self.lse = torch.zeros((n_q_heads, T), dtype=torch.float32, device=dev)
         self.dq = self.dk = self.dv = None
+
+    # -- buffers ------------------------------------------------------------------------------
+    def buffer(self, heads: int, dim: int) -> torch.Tensor:
+        """Zeroed bf16 [T, heads, dim] tensor in this object's row layout (a view when rows are padded)."""
+        T = max(self.T, 1)
+        if not self.row_pad:
+            return torch.zeros((T, heads, dim), dtype=torch.bfloat16, device=self.device)
+        base = torch.zeros((T, heads * dim + self.row_pad), dtype=torch.bfloat16, device=self.device)
+        return base[:, :heads * dim].view(T, heads, dim)
 
     # -- inputs -------------------------------------------------------------------------------
     def to_device_bf16(self, bits: np.ndarray) -> torch.Tensor:
         """uint16 bf16 bit patterns [T,H,dim] -> bf16 tensor on the device."""
-        t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(self.device)
-        return t.view(torch.bfloat16)
+        t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(self.device).view(torch.bfloat16)
+        if not self.row_pad:
+            return t
+        out = self.buffer(t.shape[1], t.shape[2])
+        out.copy_(t)
+        return out
 
     # -- calls --------------------------------------------------------------------------------
     def _stream(self) -> int:
@@ -87,9 +108,9 @@ class PackedAttention:
         if self.ws_bwd is None:
             dev, bf, T = self.device, torch.bfloat16, max(self.T, 1)
             self.ws_bwd = torch.empty(B.hbp_workspace_bytes(self.desc, B.HBP_BWD), dtype=torch.uint8, device=dev)
-            self.dq = torch.zeros((T, self.Hq, self.d_qk), dtype=bf, device=dev)
-            self.dk = torch.zeros((T, self.Hkv, self.d_qk), dtype=bf, device=dev)
-            self.dv = torch.zeros((T, self.Hkv, self.d_v), dtype=bf, device=dev)
+            self.dq = self.buffer(self.Hq, self.d_qk)
+            self.dk = self.buffer(self.Hkv, self.d_qk)
+            self.dv = self.buffer(self.Hkv, self.d_v)
 
     def backward(self, q, k, v, d_o, profile: bool = False):
         self.alloc_backward()
