@@ -220,3 +220,10 @@ def test_seeded_sweep_of_random_packs():
         print("sweep case", i, lengths, pack_len, Hkv * g, Hkv, d, e, scale, flush=True)
         full(Case(lengths, pack_len, Hkv * g, Hkv, d, e, seed=100 + i, sigma=float(rng.choice([0.5, 1.0])),
                   scale=scale, name="sweep-%d" % i))
+
+
+def test_long_sample_whose_later_key_tiles_start_below_the_top_and_wrap():
+    """41 key tiles of one sample on 8 kv heads: 32 workgroups share a kv head, so key tiles 32..40 take
+    their query blocks in the wrapped order (start below the sample's last block, skipped blocks last).
+    A second, short sample rides along.  dK/dV of every key against the oracle."""
+    full(Case([5197, 300], 5497, 8, 8, 64, 64, seed=41, name="wrap"))
