@@ -111,9 +111,19 @@ def cpu_baseline(w, cu, target_pairs=2.0e8):
     dt = time.perf_counter() - t0
     flops = len(q_heads) * pairs * (2 * (w.d_qk + w.d_v) + 2 * (3 * w.d_qk + 2 * w.d_v))
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.oracle_threads(),
-            "kind": "oracle", "seconds": dt,
+            "kind": "oracle", "seconds": dt, "cpu_model": cpu_model(),
             "sample": "%s (%d tokens, %d causal pairs), %d query heads / %d kv heads, fwd+bwd in fp64"
                       % (what, int(sum(sub_lens)), pairs, len(q_heads), len(kv_heads))}
+
+
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
 def planner_timing(n=1_000_000):
