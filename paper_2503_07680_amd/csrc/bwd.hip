@@ -429,7 +429,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
       // the end; that round ends together, the next one starts together, and so on in turns.  The
       // order is a function of the tile number alone, so the results do not depend on timing.
       // (With fewer than 8 workgroups per kv head there is little to share and the plain order is kept.)
-      const int w_share = (int)gridDim.x / p.Hkv;
+      const int w_share = (int)gridDim.x / min(p.Hkv, kNumXcd * kHeadGroup);  // kv heads in work at a time
       int skip = w_share >= 8 && ((tl.tile / w_share) & 1) ? (tl.tile % w_share) * (BN / BQ) : 0;
       skip = max(0, min(skip, nqb - 1));
       const int first_blk = nqb - 1 - skip;
