@@ -232,6 +232,8 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="workload 1..5 (default 3: the mixed 32K pack)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--heads", default="",
+                    help="Hq/Hkv override, e.g. 32/32: the chosen workload's lengths with another head layout")
     ap.add_argument("--row-pad", type=int, default=0,
                     help="extra elements (multiple of 8) at the end of every token row of Q, K, V, O and the "
                          "gradients (strides in the descriptor); default 0 = dense [T, H, dim]")
@@ -257,6 +259,10 @@ def main():
         sys.exit(1)
     H.load_library()
     w = wl.workload(args.config, args.seed)
+    if args.heads:
+        import dataclasses
+        hq, hkv = (int(x) for x in args.heads.split("/"))
+        w = dataclasses.replace(w, n_q_heads=hq, n_kv_heads=hkv, note=w.note + "; heads overridden to %d/%d" % (hq, hkv))
     pa = PackedAttention(w.lengths, w.pack_len, w.n_q_heads, w.n_kv_heads, w.d_qk, w.d_v, with_profile=True,
                          row_pad=args.row_pad)
     T = pa.T

@@ -109,7 +109,11 @@ hbp_status hbp_fwd_tile_rows(const hbp_attn_desc* desc, int32_t* rows_out);
 
 /* Bytes of device workspace a call needs (256-byte aligned base required).
  * which = HBP_FWD or HBP_BWD.  Forward: the scheduler's per-die queue counters.  Backward: two
- * sets of counters, the per-row D = rowsum(dO*O) and LSE*log2(e), both [Hq,T] fp32. */
+ * sets of counters, the per-row D = rowsum(dO*O) and LSE*log2(e), both [Hq,T] fp32; and, with
+ * fewer than 8 kv heads, fp32 partial sums of dK and dV, [parts][T][Hkv][d_qk + d_v]: the query
+ * heads of a kv head are then dealt out in `parts` runs (the smallest divisor of Hq/Hkv with
+ * Hkv * parts >= 8, else Hq/Hkv) that are separate work items, and a reduce kernel adds the parts
+ * up in a fixed order (no atomics either way). */
 hbp_status hbp_workspace_bytes(const hbp_attn_desc* desc, int32_t which, size_t* bytes_out);
 
 /* Optional per-workgroup record written by the persistent kernels when `profile` != NULL
@@ -163,7 +167,8 @@ hbp_status hbp_varlen_attn_fwd(const hbp_attn_desc* desc, const void* q, const v
  *   dV = sum_{h in group} P^T dO
  *
  * Three launches on `stream`: a pre-pass (D), the persistent key-tile kernel (dK/dV accumulated in
- * registers over the query blocks and over the query heads of each kv head) and the persistent
+ * registers over the query blocks and over the query heads of each kv head; followed by a small
+ * reduce kernel when there are fewer than 8 kv heads, see hbp_workspace_bytes) and the persistent
  * query-tile kernel (dQ; it recomputes S and dP).  No atomics: every output element is written
  * once, results are bit-stable.
  * q_tiles: the HBP_TILES_QUERY list made with hbp_tile_rows(..., HBP_FWD) (the forward's list

@@ -56,7 +56,7 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct BwdLayout {
-  size_t d_off, lse2_off, total;
+  size_t d_off, lse2_off, dk_part_off, dv_part_off, total;
 };
 
 BwdLayout bwd_layout(const hbp_attn_desc* d) {
@@ -64,7 +64,10 @@ BwdLayout bwd_layout(const hbp_attn_desc* d) {
   l.d_off = kCounterBytes;
   const size_t rows = align_up((size_t)d->n_q_heads * d->total_tokens * sizeof(float), 256);
   l.lse2_off = l.d_off + rows;
-  l.total = l.lse2_off + rows;
+  const int g = d->n_q_heads / d->n_kv_heads;
+  l.dk_part_off = l.lse2_off + rows;
+  l.dv_part_off = l.dk_part_off + align_up(hbp::bwd_partial_floats(d->total_tokens, d->n_kv_heads, g, d->d_qk) * sizeof(float), 256);
+  l.total = l.dv_part_off + align_up(hbp::bwd_partial_floats(d->total_tokens, d->n_kv_heads, g, d->d_v) * sizeof(float), 256);
   return l;
 }
 
@@ -278,6 +281,7 @@ extern "C" hbp_status hbp_varlen_attn_fwd(const hbp_attn_desc* desc, const void*
   p.scale_log2 = resolve_scale(desc) * 1.4426950408889634f;
   p.counter = static_cast<int32_t*>(workspace);
   p.prof = profile;
+  p.n_split = hbp::heads_split(p.Hkv, p.g % 2 == 0 ? p.g / 2 : p.g);  // even groups: items are pairs of heads
 
   hipStream_t hs = static_cast<hipStream_t>(stream);
   if (hbp::launch_zero_counters(p.counter, hs) != 0) return HBP_ERR_DEVICE;
@@ -341,8 +345,12 @@ extern "C" hbp_status hbp_varlen_attn_bwd(const hbp_attn_desc* desc, const void*
   p.scale = resolve_scale(desc);
   p.scale_log2 = p.scale * 1.4426950408889634f;
   p.prof = profile;
+  p.n_split = hbp::heads_split(p.Hkv, p.g);
+  p.n_split_dq = p.n_split;
+  p.dk_part = reinterpret_cast<float*>(ws + lay.dk_part_off);
+  p.dv_part = reinterpret_cast<float*>(ws + lay.dv_part_off);
 
-  const int grid_dkdv = grid_for((int64_t)n_kv_tiles * p.Hkv, 1);
+  const int grid_dkdv = grid_for((int64_t)n_kv_tiles * p.Hkv * p.n_split, 1);
   const int grid_dq = grid_for((int64_t)n_q_tiles * p.Hq, 2);
   hipEvent_t ev[4] = {g_events[HBP_BWD][0], g_events[HBP_BWD][1], g_events[HBP_BWD_DQ][0], g_events[HBP_BWD_DQ][1]};
   if (hbp::launch_bwd(desc->d_qk, desc->d_v, p, grid_dq, grid_dkdv, static_cast<hipStream_t>(stream), ev) != 0)

@@ -105,7 +105,7 @@ __global__ __launch_bounds__(kThreads, DQK <= 128 ? 2 : 1) void bwd_dq_kernel(co
   const uint32_t k_stride_b = (uint32_t)p.k_st * 2, v_stride_b = (uint32_t)p.v_st * 2;
 
   ProfAcc pa;
-  const WorkQueues wq{p.counter_dq, p.n_q_tiles, p.Hkv, p.g};
+  const WorkQueues wq{p.counter_dq, p.n_q_tiles, p.Hkv * p.n_split_dq, p.g / p.n_split_dq};
   int q_cur = xcc_id_reg() & (kNumXcd - 1), q_tried = 0;
   for (;;) {
     int tile_idx, h;
@@ -387,11 +387,16 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
   __syncthreads();
 
   ProfAcc pa;
-  const WorkQueues wq{p.counter, p.n_tiles, p.Hkv, 1};
+  // Work item = (key tile, kv head, part of its query heads): with n_split > 1 the g heads of a kv head
+  // are cut into n_split runs of g_item heads, each an item of its own.
+  const WorkQueues wq{p.counter, p.n_tiles, p.Hkv * p.n_split, 1};
+  const int g_item = p.g / p.n_split;
   int q_cur = xcc_id_reg() & (kNumXcd - 1), q_tried = 0;
   for (;;) {
-    int tile_idx, kh;
-    if (!next_item(wq, (int*)smem, tid, q_cur, q_tried, tile_idx, kh)) break;
+    int tile_idx, vh;
+    if (!next_item(wq, (int*)smem, tid, q_cur, q_tried, tile_idx, vh)) break;
+    const int kh = vh / p.n_split, part = vh - kh * p.n_split;
+    const int head0 = vh * g_item;  // first query head of the item
     prof_begin(pa, p.prof, tid);
 
     const hbp_tile tl = p.tiles[tile_idx];
@@ -414,7 +419,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
 
       const int qb_start = (k0_in / BQ) * BQ;
       const int nqb = (s_len - qb_start + BQ - 1) / BQ;
-      const int n_steps = nqb * p.g;
+      const int n_steps = nqb * g_item;
 
       // Step order: the query blocks from the LAST one of the sample down to the tile's own, and for each
       // block the g query heads of the group.  Every key tile of a sample needs a suffix of the same
@@ -429,7 +434,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
       // the end; that round ends together, the next one starts together, and so on in turns.  The
       // order is a function of the tile number alone, so the results do not depend on timing.
       // (With fewer than 8 workgroups per kv head there is little to share and the plain order is kept.)
-      const int w_share = (int)gridDim.x / min(p.Hkv, kNumXcd * kHeadGroup);  // kv heads in work at a time
+      const int w_share = (int)gridDim.x / min(p.Hkv * p.n_split, kNumXcd * kHeadGroup);  // heads in work at a time
       int skip = w_share >= 8 && ((tl.tile / w_share) & 1) ? (tl.tile % w_share) * (BN / BQ) : 0;
       skip = max(0, min(skip, nqb - 1));
       const int first_blk = nqb - 1 - skip;
@@ -438,9 +443,9 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
       // Copies are issued in step order; the source pointers of the next block to copy are carried
       // along instead of being recomputed from the step number.
       const int64_t first_row = (int64_t)s0 + qb_start + (int64_t)first_blk * BQ;
-      const uint16_t* q_blk = p.q + first_row * p.q_st + (int64_t)(kh * p.g) * p.q_sh;
-      const uint16_t* o_blk = p.d_o + first_row * p.o_st + (int64_t)(kh * p.g) * p.o_sh;
-      const float* row_blk = (wave == 0 ? p.lse2 : p.D) + (int64_t)(kh * p.g) * p.T + first_row;
+      const uint16_t* q_blk = p.q + first_row * p.q_st + (int64_t)head0 * p.q_sh;
+      const uint16_t* o_blk = p.d_o + first_row * p.o_st + (int64_t)head0 * p.o_sh;
+      const float* row_blk = (wave == 0 ? p.lse2 : p.D) + (int64_t)head0 * p.T + first_row;
       const uint16_t* q_src = q_blk;
       const uint16_t* o_src = o_blk;
       const float* row_src = row_blk;
@@ -456,7 +461,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
           const float* dst = (wave == 0 ? lse_lds : d_lds) + buf * BQ;
           async_copy4(row_src, (uint32_t)row * 4u, lds_address(dst));
         }
-        if (++head_next == p.g) {  // on to the block before; from the tile's own block to the sample's last
+        if (++head_next == g_item) {  // on to the block before; from the tile's own block to the sample's last
           head_next = 0;
           const int64_t jump = blk_next == 0 ? (int64_t)(nqb - 1) * BQ : -(int64_t)BQ;
           blk_next = blk_next == 0 ? nqb - 1 : blk_next - 1;
@@ -511,7 +516,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
         // the step's buffer is a compile-time constant: it goes into the immediate offset of every LDS
         // read (two copies of the step's code instead of 34 address updates per step)
         constexpr int BUF = decltype(buf_tag)::value;
-        const int qb = qb_start + block_of(step / p.g) * BQ;
+        const int qb = qb_start + block_of(step / g_item) * BQ;
         auto sd_load = [&](int sub) {
           return [&, sub](int i) {
             Frag a;
@@ -708,7 +713,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
         do_step(step + 1, std::integral_constant<int, 1>{});
       }
 
-      if (key_valid) {
+      if (key_valid && p.n_split == 1) {
         uint16_t* dkp = p.dk + (int64_t)my_key * p.k_st + (int64_t)kh * p.k_sh + 4 * hh;
         uint16_t* dvp = p.dv + (int64_t)my_key * p.v_st + (int64_t)kh * p.v_sh + 4 * hh;
 #pragma unroll
@@ -728,11 +733,66 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
                        pack_bf16(dvt[eb][4 * b + 2], dvt[eb][4 * b + 3])};
             *(u32x2*)(dvp + 32 * eb + 8 * b) = w;
           }
+      } else if (key_valid) {
+        // this part's sums, fp32, [part][key][kv head][dim]; the reduce kernel adds the parts up
+        const int64_t row = ((int64_t)part * p.T + my_key) * p.Hkv + kh;
+        float* dkp = p.dk_part + row * DQK + 4 * hh;
+        float* dvp = p.dv_part + row * DV + 4 * hh;
+        const float ksc = -p.scale;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+          for (int b = 0; b < 4; ++b)
+            *(f32x4*)(dkp + 32 * db + 8 * b) = f32x4{dkt[db][4 * b] * ksc, dkt[db][4 * b + 1] * ksc,
+                                                       dkt[db][4 * b + 2] * ksc, dkt[db][4 * b + 3] * ksc};
+#pragma unroll
+        for (int eb = 0; eb < NEB; ++eb)
+#pragma unroll
+          for (int b = 0; b < 4; ++b)
+            *(f32x4*)(dvp + 32 * eb + 8 * b) = f32x4{dvt[eb][4 * b], dvt[eb][4 * b + 1], dvt[eb][4 * b + 2], dvt[eb][4 * b + 3]};
       }
     }
     prof_end(pa, p.prof, tid);
   }
   prof_write(pa, p.prof, tid);
+}
+
+// dK, dV = sum over the parts of the partial sums of the key-tile kernel, in part order.  One workgroup
+// per key tile of the worklist (only rows covered by a tile are written, as without parts); a thread
+// handles four consecutive dims of one (key, kv head).
+template <int DQK, int DV>
+__global__ __launch_bounds__(kThreads) void bwd_reduce_parts_kernel(const BwdParams p) {
+  const hbp_tile tl = p.tiles[blockIdx.x];
+  if (tl.sample < 0 || tl.sample >= p.n_samples) return;
+  const int s0 = p.cu[tl.sample], s1 = p.cu[tl.sample + 1];
+  if (!(s0 >= 0 && s1 <= p.T && s0 <= tl.row_begin && tl.row_begin < tl.row_end && tl.row_end <= s1 &&
+        tl.row_end - tl.row_begin <= 128))
+    return;
+  constexpr int QK4 = DQK / 4, V4 = DV / 4;
+  const int n_rows = tl.row_end - tl.row_begin;
+  const int64_t n_units = (int64_t)n_rows * p.Hkv * (QK4 + V4);
+  for (int64_t u = threadIdx.x; u < n_units; u += kThreads) {
+    const int c = (int)(u % (QK4 + V4));
+    const int64_t rk = u / (QK4 + V4);
+    const int kh = (int)(rk % p.Hkv);
+    const int64_t key = tl.row_begin + rk / p.Hkv;
+    const bool is_k = c < QK4;
+    const int dim = is_k ? DQK : DV, x = 4 * (is_k ? c : c - QK4);
+    const float* src = (is_k ? p.dk_part : p.dv_part) + (key * p.Hkv + kh) * dim + x;
+    const int64_t part_stride = (int64_t)p.T * p.Hkv * dim;
+    f32x4 acc = *(const f32x4*)src;
+    for (int part = 1; part < p.n_split; ++part) {
+      const f32x4 v = *(const f32x4*)(src + part * part_stride);
+      acc[0] += v[0]; acc[1] += v[1]; acc[2] += v[2]; acc[3] += v[3];
+    }
+    uint16_t* dst = is_k ? p.dk + key * p.k_st + (int64_t)kh * p.k_sh + x : p.dv + key * p.v_st + (int64_t)kh * p.v_sh + x;
+    *(u32x2*)dst = u32x2{pack_bf16(acc[0], acc[1]), pack_bf16(acc[2], acc[3])};
+  }
+}
+
+size_t bwd_partial_floats(int T, int Hkv, int g, int dim) {
+  const int n_split = heads_split(Hkv, g);
+  return n_split > 1 ? (size_t)n_split * (size_t)T * (size_t)Hkv * (size_t)dim : 0;
 }
 
 // D[h,r] = sum_x dO[r,h,x] O[r,h,x], LSE2 = LSE*log2(e); resets both scheduler counters.
@@ -791,6 +851,11 @@ static int launch_bwd_t(const BwdParams& p, int grid_dq, int grid_dkdv, hipStrea
     hipLaunchKernelGGL((bwd_dkdv_kernel<DQK, DV>), dim3(grid_dkdv), dim3(kThreads), lds_dkdv, s, p);
     e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
+    if (p.n_split > 1) {
+      hipLaunchKernelGGL((bwd_reduce_parts_kernel<DQK, DV>), dim3(p.n_tiles), dim3(kThreads), 0, s, p);
+      e = hipGetLastError();
+      if (e != hipSuccess) return (int)e;
+    }
     if (ev[1] && hipEventRecord(ev[1], s) != hipSuccess) return (int)hipErrorInvalidValue;
   }
   if (grid_dq > 0) {

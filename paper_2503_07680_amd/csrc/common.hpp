@@ -399,6 +399,7 @@ struct FwdParams {
   float scale_log2;  // softmax scale * log2(e)
   int32_t* counter;
   hbp_profile_rec* prof;
+  int32_t n_split;   // the query heads of a kv head are dealt to the dies in this many parts (see heads_split)
 };
 
 struct BwdParams {
@@ -415,7 +416,21 @@ struct BwdParams {
   float scale, scale_log2;
   int32_t *counter, *counter_dq;
   hbp_profile_rec *prof, *prof_dq;
+  // With fewer kv heads than dies the g query heads of a kv head are cut into n_split parts, each a
+  // work item of its own (so that every die has a queue and no item loops over too many heads).  In
+  // the dK/dV kernel the parts of a kv head then produce partial sums: fp32, [n_split][T][Hkv][dim],
+  // added up in part order by a reduce kernel.
+  int32_t n_split, n_split_dq;
+  float *dk_part, *dv_part;
 };
+
+// In how many parts the `units` schedulable units of a kv head (query heads, or pairs of them) are
+// dealt out: the smallest divisor of units that gives every die a queue, else units itself.
+inline int heads_split(int n_kv_heads, int units) {
+  for (int s = 1; s <= units; ++s)
+    if (units % s == 0 && n_kv_heads * s >= 8) return s;
+  return units;
+}
 
 struct CeParams {  // packed cross-entropy
   const uint16_t* logits;
@@ -441,6 +456,7 @@ int launch_fwd(int d_qk, int d_v, const FwdParams& p, int tile_rows, int n_cu, h
                hipEvent_t ev1);
 // ev: {dkdv start, dkdv stop, dq start, dq stop}, entries may be null
 int launch_bwd(int d_qk, int d_v, const BwdParams& p, int grid_dq, int grid_dkdv, hipStream_t s, hipEvent_t* ev);
+size_t bwd_partial_floats(int T, int Hkv, int g, int dim);  // per tensor; 0 when the dK/dV kernel needs no partial sums
 int launch_zero_counters(int32_t* counters, hipStream_t s);  // the kNumXcd forward counters
 int launch_packed_ce(const CeParams& p, int n_cu, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
 

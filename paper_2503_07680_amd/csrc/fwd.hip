@@ -300,7 +300,7 @@ __global__ __launch_bounds__(kThreads * HP * TP, 2 / (HP * TP)) void fwd_kernel(
   uint32_t n_done = 0;
   uint64_t t_first = 0, t_last = 0, t_busy = 0;
 
-  const WorkQueues wq{p.counter, p.n_tiles, p.Hkv, p.g / HP};
+  const WorkQueues wq{p.counter, p.n_tiles, p.Hkv * p.n_split, p.g / HP / p.n_split};
   int q_cur = xcc_id_reg() & (kNumXcd - 1), q_tried = 0;
   for (;;) {
     int tile_idx, h;

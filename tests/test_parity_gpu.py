@@ -227,3 +227,30 @@ def test_long_sample_whose_later_key_tiles_start_below_the_top_and_wrap():
     their query blocks in the wrapped order (start below the sample's last block, skipped blocks last).
     A second, short sample rides along.  dK/dV of every key against the oracle."""
     full(Case([5197, 300], 5497, 8, 8, 64, 64, seed=41, name="wrap"))
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(8, 1), (12, 3), (8, 8)])
+def test_few_kv_heads_split_their_query_heads_and_partial_tile_lists_leave_rows_alone(Hq, Hkv):
+    """With fewer kv heads than dies the query heads of a kv head are dealt out in parts (dK/dV then come
+    from partial sums and a reduce kernel).  All outputs against the oracle; and with a key-tile list
+    that leaves tiles out, the dK/dV rows of those tiles keep what they held, in either form."""
+    import torch
+    from paper_2503_07680_amd import binding as B
+    case = Case([700, 130, 1, 333], 1164, Hq, Hkv, 128, 128, seed=51, name="split-%d-%d" % (Hq, Hkv))
+    pa, dev, out = full(case)
+    keep = [i for i in range(len(pa.kv_tiles)) if i % 3 != 1]
+    left_out = [pa.kv_tiles[i] for i in range(len(pa.kv_tiles)) if i % 3 == 1]
+    tiles_dev = torch.from_numpy(np.ascontiguousarray(pa.kv_tiles[keep])).to(pa.device)
+    sentinel = 3.0
+    dk = torch.full_like(pa.dk, sentinel)
+    dv = torch.full_like(pa.dv, sentinel)
+    B.hbp_varlen_attn_bwd(pa.desc, dev["q"], dev["k"], dev["v"], pa.o, pa.lse, dev["do"], pa.cu_dev, pa.q_tiles_dev,
+                          len(pa.q_tiles), tiles_dev, len(keep), pa.dq, dk, dv, pa.ws_bwd, None, None,
+                          int(torch.cuda.current_stream().cuda_stream))
+    torch.cuda.synchronize()
+    covered = torch.zeros(pa.T, dtype=torch.bool, device=pa.device)
+    for i in keep:
+        covered[int(pa.kv_tiles[i][2]):int(pa.kv_tiles[i][3])] = True
+    assert len(left_out) > 0 and bool((~covered).any())
+    assert torch.equal(dk[covered], pa.dk[covered]) and torch.equal(dv[covered], pa.dv[covered])
+    assert bool((dk[~covered] == sentinel).all()) and bool((dv[~covered] == sentinel).all())
