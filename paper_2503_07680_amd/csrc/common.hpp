@@ -336,8 +336,10 @@ struct Taken {
 // One thread takes the next item.  q_cur / q_tried: that thread's cursor over the queues.  A real
 // call, everything passed and returned by value in registers: inlined into the persistent kernels
 // its temporaries cost them registers they do not have (two of them would spill).
+// steal_stride (odd): how the cursor moves on from an exhausted queue; different workgroups of a die use
+// different strides, so they do not all descend on the same other queue.
 __device__ __attribute__((noinline)) Taken take_item(int32_t* counters, int n_tiles, int Hkv, int per_kv, int q_cur,
-                                                      int q_tried) {
+                                                      int q_tried, int steal_stride) {
   while (q_tried < kNumXcd) {
     const int nk = Hkv > q_cur ? (Hkv - q_cur + kNumXcd - 1) / kNumXcd : 0;  // kv heads of this die
     const int len = n_tiles * nk * per_kv;
@@ -358,7 +360,7 @@ __device__ __attribute__((noinline)) Taken take_item(int32_t* counters, int n_ti
                      q_cur, q_tried};
       }
     }
-    q_cur = (q_cur + 1) & (kNumXcd - 1);
+    q_cur = (q_cur + steal_stride) & (kNumXcd - 1);
     ++q_tried;
   }
   return Taken{-1, 0, q_cur, q_tried};
@@ -375,7 +377,8 @@ __device__ __forceinline__ bool next_item(const WorkQueues& wq, int* slot, int t
                                           int& tile_idx, int& head) {
   __syncthreads();  // all LDS reads of the previous item are finished
   if (tid == 0) {
-    const Taken tk = take_item(wq.counters, wq.n_tiles, wq.Hkv, wq.per_kv, q_cur, q_tried);
+    const Taken tk = take_item(wq.counters, wq.n_tiles, wq.Hkv, wq.per_kv, q_cur, q_tried,
+                               2 * ((blockIdx.x >> 3) & 3) + 1);
     q_cur = tk.q_cur;
     q_tried = tk.q_tried;
     ((volatile int*)slot)[0] = tk.tile_idx;
