@@ -254,3 +254,10 @@ def test_few_kv_heads_split_their_query_heads_and_partial_tile_lists_leave_rows_
     assert len(left_out) > 0 and bool((~covered).any())
     assert torch.equal(dk[covered], pa.dk[covered]) and torch.equal(dv[covered], pa.dv[covered])
     assert bool((dk[~covered] == sentinel).all()) and bool((dv[~covered] == sentinel).all())
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(24, 24), (40, 40), (34, 17)])
+def test_head_counts_that_leave_dies_with_uneven_and_odd_numbers_of_kv_heads(Hq, Hkv):
+    """24, 40 and 17 kv heads over 8 dies: 3, 5, and 2-or-3 kv heads per die, taken two at a time with a
+    smaller last group.  Every head must be served exactly once (all outputs against the oracle)."""
+    full(Case([300, 129, 64, 7], 500, Hq, Hkv, 64, 64, seed=61, name="heads-%d-%d" % (Hq, Hkv)))
