@@ -371,23 +371,35 @@ struct WorkQueues {
   int n_tiles, Hkv, per_kv;  // per_kv: heads per kv head inside one item group (g, or 1)
 };
 
+// Workgroup barrier that orders LDS traffic only: waits for this wave's LDS operations, not for its
+// outstanding global stores (the results a previous item is still writing out).
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // Workgroup-wide fetch of the next item: thread 0 takes it, everybody reads it back as scalars.
 // slot: two ints of LDS that nobody else touches between the surrounding barriers.
 __device__ __forceinline__ bool next_item(const WorkQueues& wq, int* slot, int tid, int& q_cur, int& q_tried,
                                           int& tile_idx, int& head) {
-  __syncthreads();  // all LDS reads of the previous item are finished
+  // the slot is addressed as LDS (not through a generic pointer: that becomes flat accesses, each
+  // followed by a wait for every outstanding global store of the previous item)
+  volatile __attribute__((address_space(3))) int* const box =
+      (volatile __attribute__((address_space(3))) int*)(uintptr_t)lds_address(slot);
+  lds_barrier();  // all LDS reads of the previous item are finished
   if (tid == 0) {
     const Taken tk = take_item(wq.counters, wq.n_tiles, wq.Hkv, wq.per_kv, q_cur, q_tried,
                                2 * ((blockIdx.x >> 3) & 3) + 1);
     q_cur = tk.q_cur;
     q_tried = tk.q_tried;
-    ((volatile int*)slot)[0] = tk.tile_idx;
-    ((volatile int*)slot)[1] = tk.head;
+    box[0] = tk.tile_idx;
+    box[1] = tk.head;
   }
-  __syncthreads();
-  tile_idx = __builtin_amdgcn_readfirstlane(((volatile int*)slot)[0]);
-  head = __builtin_amdgcn_readfirstlane(((volatile int*)slot)[1]);
-  __syncthreads();
+  lds_barrier();
+  tile_idx = __builtin_amdgcn_readfirstlane(box[0]);
+  head = __builtin_amdgcn_readfirstlane(box[1]);
+  lds_barrier();
   return tile_idx >= 0;
 }
 
