@@ -309,16 +309,10 @@ __global__ __launch_bounds__(kThreads, DQK <= 128 ? 2 : 1) void bwd_dq_kernel(co
       }
       if (cur_buf) point_offsets_at(0);
 
-      if (row_valid) {
-        uint16_t* dqp = p.dq + (int64_t)my_row * p.q_st + (int64_t)h * p.q_sh + 4 * hh;
+      {
+        uint16_t* dqp = p.dq + (int64_t)my_row * p.q_st + (int64_t)h * p.q_sh;
 #pragma unroll
-        for (int db = 0; db < NDB; ++db)
-#pragma unroll
-          for (int b = 0; b < 4; ++b) {
-            u32x2 w = {pack_bf16(dqacc[db][4 * b] * p.scale, dqacc[db][4 * b + 1] * p.scale),
-                       pack_bf16(dqacc[db][4 * b + 2] * p.scale, dqacc[db][4 * b + 3] * p.scale)};
-            *(u32x2*)(dqp + 32 * db + 8 * b) = w;
-          }
+        for (int db = 0; db < NDB; ++db) store_block_bf16(dqp + 32 * db, dqacc[db], p.scale, hh, row_valid);
       }
     }
     prof_end(pa, p.prof_dq, tid);
@@ -713,26 +707,13 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
         do_step(step + 1, std::integral_constant<int, 1>{});
       }
 
-      if (key_valid && p.n_split == 1) {
-        uint16_t* dkp = p.dk + (int64_t)my_key * p.k_st + (int64_t)kh * p.k_sh + 4 * hh;
-        uint16_t* dvp = p.dv + (int64_t)my_key * p.v_st + (int64_t)kh * p.v_sh + 4 * hh;
+      if (p.n_split == 1) {
+        uint16_t* dkp = p.dk + (int64_t)my_key * p.k_st + (int64_t)kh * p.k_sh;
+        uint16_t* dvp = p.dv + (int64_t)my_key * p.v_st + (int64_t)kh * p.v_sh;
 #pragma unroll
-        for (int db = 0; db < NDB; ++db)
+        for (int db = 0; db < NDB; ++db) store_block_bf16(dkp + 32 * db, dkt[db], -p.scale, hh, key_valid);
 #pragma unroll
-          for (int b = 0; b < 4; ++b) {
-            const float ksc = -p.scale;
-            u32x2 w = {pack_bf16(dkt[db][4 * b] * ksc, dkt[db][4 * b + 1] * ksc),
-                       pack_bf16(dkt[db][4 * b + 2] * ksc, dkt[db][4 * b + 3] * ksc)};
-            *(u32x2*)(dkp + 32 * db + 8 * b) = w;
-          }
-#pragma unroll
-        for (int eb = 0; eb < NEB; ++eb)
-#pragma unroll
-          for (int b = 0; b < 4; ++b) {
-            u32x2 w = {pack_bf16(dvt[eb][4 * b], dvt[eb][4 * b + 1]),
-                       pack_bf16(dvt[eb][4 * b + 2], dvt[eb][4 * b + 3])};
-            *(u32x2*)(dvp + 32 * eb + 8 * b) = w;
-          }
+        for (int eb = 0; eb < NEB; ++eb) store_block_bf16(dvp + 32 * eb, dvt[eb], 1.0f, hh, key_valid);
       } else if (key_valid) {
         // this part's sums, fp32, [part][key][kv head][dim]; the reduce kernel adds the parts up
         const int64_t row = ((int64_t)part * p.T + my_key) * p.Hkv + kh;

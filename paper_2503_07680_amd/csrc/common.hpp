@@ -80,6 +80,24 @@ __device__ __forceinline__ float max_with_other_half(float x) {
   return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
+// Store one 32x32 accumulator block as bf16: the lane's column (a query or key row of the output, at
+// `row`: dim 0 of the block's 32 dims) and, of its 16 values, element 4b+v = dim 8b + 4hh + v.  The two
+// half-waves exchange every second group of four, so that a lane ends up with 8 consecutive dims and
+// writes 16 bytes at a time (two stores per block instead of four).  Called by all lanes (the exchange
+// needs both halves); only lanes with `valid` store.
+__device__ __forceinline__ void store_block_bf16(uint16_t* row, const f32x16& acc, float scale, int hh, bool valid) {
+#pragma unroll
+  for (int bp = 0; bp < 2; ++bp) {
+    const int e = 8 * bp;  // elements e..e+3: dims 16bp + 4hh + v; e+4..e+7: dims 16bp + 8 + 4hh + v
+    const uint32_t y0 = pack_bf16(acc[e] * scale, acc[e + 1] * scale), y1 = pack_bf16(acc[e + 2] * scale, acc[e + 3] * scale);
+    const uint32_t x0 = pack_bf16(acc[e + 4] * scale, acc[e + 5] * scale), x1 = pack_bf16(acc[e + 6] * scale, acc[e + 7] * scale);
+    const auto s0 = __builtin_amdgcn_permlane32_swap(y0, x0, false, false);
+    const auto s1 = __builtin_amdgcn_permlane32_swap(y1, x1, false, false);
+    // lower half-wave: dims 16bp + 0..7, upper: 16bp + 8..15
+    if (valid) *(u32x4*)(row + 16 * bp + 8 * hh) = u32x4{s0[0], s1[0], s0[1], s1[1]};
+  }
+}
+
 // ---- LDS tiles in their natural [row][dim] layout, 16-byte chunks XOR-swizzled -----------------
 // Chunk c of row r sits at chunk position c ^ f(r).  Two access patterns have to stay free of bank
 // conflicts (a bank line is 16 chunks): 16 consecutive rows read at one chunk index (row-major MFMA

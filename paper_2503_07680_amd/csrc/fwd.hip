@@ -459,18 +459,12 @@ __global__ __launch_bounds__(kThreads * HP * TP, 2 / (HP * TP)) void fwd_kernel(
 
       // finalise: O = acc / l, LSE = (m + log2 l) * ln 2
       const float l_tot = w.l_run + xor32(w.l_run);
-      if (row_valid) {
+      {
         const float inv = 1.f / l_tot;
-        uint16_t* op = p.o + (int64_t)my_row * p.o_st + (int64_t)h * p.o_sh + 4 * hh;
+        uint16_t* op = p.o + (int64_t)my_row * p.o_st + (int64_t)h * p.o_sh;
 #pragma unroll
-        for (int eb = 0; eb < NEB; ++eb)
-#pragma unroll
-          for (int b = 0; b < 4; ++b) {
-            u32x2 wv = {pack_bf16(w.oacc[eb][4 * b] * inv, w.oacc[eb][4 * b + 1] * inv),
-                        pack_bf16(w.oacc[eb][4 * b + 2] * inv, w.oacc[eb][4 * b + 3] * inv)};
-            *(u32x2*)(op + 32 * eb + 8 * b) = wv;
-          }
-        if (hh == 0)
+        for (int eb = 0; eb < NEB; ++eb) store_block_bf16(op + 32 * eb, w.oacc[eb], inv, hh, row_valid);
+        if (row_valid && hh == 0)
           p.lse[(int64_t)h * p.T + my_row] = (w.m_run + log2f(l_tot)) * 0.6931471805599453f;
       }
     }
