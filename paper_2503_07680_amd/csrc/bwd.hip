@@ -424,8 +424,8 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
       // of a long sample w at a time, longest first.  Tiles 0..w-1 start together and end BN/BQ blocks
       // apart (each is that much shorter than the one before); their workgroups then take tiles
       // w..2w-1 one after the other, BN/BQ blocks apart.  Such a tile starts as many blocks below the top
-      // as it starts late (where the first of its round is by then) and does the blocks it skipped at
-      // the end; that round ends together, the next one starts together, and so on in turns.  The
+      // as it starts late (where the first tile of its set is by then) and does the blocks it skipped at
+      // the end; that set of w tiles ends together, the next one starts together, and so on in turns.  The
       // order is a function of the tile number alone, so the results do not depend on timing.
       // (With fewer than 8 workgroups per kv head there is little to share and the plain order is kept.)
       const int w_share = (int)gridDim.x / min(p.Hkv * p.n_split, kNumXcd * kHeadGroup);  // heads in work at a time

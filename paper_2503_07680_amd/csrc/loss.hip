@@ -348,7 +348,7 @@ __global__ __launch_bounds__(kCeThreads) void ce_reduce_kernel(const CeParams p)
 }
 
 // Workgroups resident at once per compute unit.  The main kernel's grid is that times the compute
-// units: a persistent loop over rows; a second round of workgroups would start with an empty pipeline.
+// units: a persistent loop over rows; a second batch of workgroups would start with an empty pipeline.
 template <int NCH, bool HOLD, bool WITH_GRAD>
 static int main_per_cu() {
   static int per_cu = 0;  // same on every device of this part
