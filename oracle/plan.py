@@ -37,12 +37,14 @@ def pack_plan(lengths: Sequence[int], pack_len: int, tile_rows: int, kind: int):
     """
     if pack_len <= 0 or tile_rows <= 0 or kind not in (0, 1):
         raise ValueError("bad argument")
+    # a sample has at least one token: a length <= 0 anywhere in the list is an error, also behind the
+    # point where the pack is already full (the paper is silent; the list as a whole is the input)
+    if any(int(s) <= 0 for s in lengths):
+        raise ValueError("non-positive length")
     taken: List[int] = []
     filled = 0
     consumed = 0
     for s in lengths:
-        if s <= 0:
-            raise ValueError("non-positive length")
         if filled == pack_len:
             break
         take = min(int(s), pack_len - filled)

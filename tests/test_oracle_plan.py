@@ -59,6 +59,11 @@ def test_truncation_and_underfull():
         pack_plan([10, 0, 5], 64, 16, 0)
     with pytest.raises(ValueError):
         pack_plan([10], 0, 16, 0)
+    # a non-positive length is an error wherever it stands, also behind the point where the pack is full
+    with pytest.raises(ValueError):
+        pack_plan([4, 4, 0], 4, 16, 0)
+    with pytest.raises(ValueError):
+        pack_plan([4, 4, -3], 8, 16, 1)
 
 
 @pytest.mark.parametrize("kind", [0, 1])

@@ -52,10 +52,12 @@ def test_many_tiny_samples_and_single_sample():
 
 
 def test_error_codes():
-    for bad in ([3, 0, 4], [3, -1]):
+    for bad, pack_len in (([3, 0, 4], 64), ([3, -1], 64), ([4, 4, 0], 4), ([4, 4, -3], 8)):
         with pytest.raises(H.HbpError) as e:
-            H.hbp_pack_plan(bad, 64, 16, 0)
+            H.hbp_pack_plan(bad, pack_len, 16, 0)
         assert e.value.status == 1
+        with pytest.raises(ValueError):          # the oracle rejects the same lists (also a bad length
+            oracle_plan(bad, pack_len, 16, 0)    # that lies behind the point where the pack is full)
     for args in (([4], 0, 16, 0), ([4], 16, 0, 0), ([4], 16, 16, 2)):
         with pytest.raises(H.HbpError) as e:
             H.hbp_pack_plan(*args)
