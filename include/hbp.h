@@ -33,7 +33,8 @@ typedef int32_t hbp_status;
 enum {
   HBP_OK = 0,
   HBP_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, bad enum value            */
-  HBP_ERR_SHAPE = 2,       /* Hq % Hkv != 0, stride smaller than the row it must hold    */
+  HBP_ERR_SHAPE = 2,       /* Hq % Hkv != 0, stride smaller than the row it must hold,
+                            * not a multiple of 8, or a token stride above 2^22 elements  */
   HBP_ERR_UNSUPPORTED = 3, /* head dims outside the supported set                        */
   HBP_ERR_CAPACITY = 4,    /* an output array of the planner is too small                */
   HBP_ERR_WORKSPACE = 5,   /* workspace missing, misaligned or smaller than required     */
@@ -89,7 +90,10 @@ typedef struct {
                           * hbp_tile_rows value; hbp_fwd_tile_rows() says which larger size, if
                           * any, the forward kernel of this head layout also takes           */
   /* strides in elements; 0 = dense ([T,H,dim] contiguous).  dQ/dK/dV/dO/O use the o_ and
-   * the q_/k_/v_ strides of the tensor they mirror (dO and O share o_*).               */
+   * the q_/k_/v_ strides of the tensor they mirror (dO and O share o_*).  Every stride is a
+   * multiple of 8 (16-byte vector accesses) and holds its row; a token stride is at most
+   * 2^22 = 4194304 elements (the kernels address the rows of a tile in 32 bits):
+   * HBP_ERR_SHAPE otherwise.                                                           */
   int64_t q_stride_t, q_stride_h, k_stride_t, k_stride_h;
   int64_t v_stride_t, v_stride_h, o_stride_t, o_stride_h;
 } hbp_attn_desc;

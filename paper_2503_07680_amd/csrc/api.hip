@@ -9,6 +9,7 @@ namespace {
 
 constexpr int kNumCU = 256;          // MI355X: 8 accelerator dies x 32 compute units
 constexpr size_t kCounterBytes = 2048;  // two sets of 8 per-die counters, 128 bytes apart
+constexpr int64_t kMaxTokenStride = int64_t{1} << 22;  // elements; see check_desc
 constexpr int kTileRows = 128;       // rows per query / key tile of every kernel (the forward also takes 256)
 
 bool dims_supported(int d_qk, int d_v) {
@@ -47,6 +48,11 @@ hbp_status check_desc(const hbp_attn_desc* d, Strides* st) {
   if (st->q_sh < d->d_qk || st->k_sh < d->d_qk || st->v_sh < d->d_v || st->o_sh < d->d_v)
     return HBP_ERR_SHAPE;
   if (st->q_st < d->d_qk || st->k_st < d->d_qk || st->v_st < d->d_v || st->o_st < d->d_v)
+    return HBP_ERR_SHAPE;
+  // The kernels form (row of a tile) * (token stride in bytes) in 32 bits, the tile copies with a 24-bit
+  // multiply: a token stride must stay below 2^23 elements.  The bound is 2^22 (8 MiB per token).
+  if (st->q_st > kMaxTokenStride || st->k_st > kMaxTokenStride || st->v_st > kMaxTokenStride ||
+      st->o_st > kMaxTokenStride)
     return HBP_ERR_SHAPE;
   return HBP_OK;
 }

@@ -65,11 +65,26 @@ def test_tile_rows_and_workspace_queries():
     (dict(fwd_tile_rows=256), 1),               # 256-row tiles need an odd group size (here 2)
     (dict(q_stride_h=64), 2),                   # head stride smaller than the head
     (dict(k_stride_t=100), 2),                  # not a multiple of 8 elements
+    (dict(q_stride_t=(1 << 22) + 8), 2),        # token stride beyond what the kernels address in 32 bits
+    (dict(v_stride_t=1 << 23), 2),
+    (dict(o_stride_t=1 << 40), 2),
 ])
 def test_descriptor_validation(kw, status):
     with pytest.raises(H.HbpError) as e:
         H.hbp_workspace_bytes(desc(**kw), H.HBP_BWD)
     assert e.value.status == status
+
+
+def test_largest_token_stride_is_accepted_and_the_launch_entry_points_check_it_too():
+    lib = H.load_library()
+    ok = desc(q_stride_t=1 << 22, k_stride_t=1 << 22, v_stride_t=1 << 22, o_stride_t=1 << 22)
+    assert H.hbp_workspace_bytes(ok, H.HBP_FWD) >= 4
+    bad = desc(k_stride_t=1 << 23)
+    fake = 0x1000
+    assert lib.hbp_varlen_attn_fwd(ctypes.byref(bad), fake, fake, fake, fake, fake, 1, fake, fake, fake, 1 << 20,
+                                   None, None) == 2
+    assert lib.hbp_varlen_attn_bwd(ctypes.byref(bad), fake, fake, fake, fake, fake, fake, fake, fake, 1, fake, 1,
+                                   fake, fake, fake, fake, 1 << 30, None, None, None) == 2
 
 
 def test_launch_entry_points_reject_bad_arguments_before_touching_the_device():

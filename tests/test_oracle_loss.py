@@ -89,3 +89,22 @@ def test_weights_and_a_sample_without_loss_tokens():
     np.testing.assert_allclose(L.token_weights(y, cu, L.STABLE, 4.0), np.where(y >= 0, 1 / 12, 0))
     with pytest.raises(ValueError):
         L.token_weights(y, cu, 7)
+
+
+def test_label_at_or_above_the_vocabulary_size_is_a_token_without_loss():
+    """One reading for both sides: a label outside [0, V) behaves exactly like a negative one (no loss,
+    zero gradient row, not counted in T_i)."""
+    rng = np.random.default_rng(9)
+    V = 11
+    z = rng.normal(0, 2, (8, V))
+    y = np.array([1, V, 2, -1, V + 5, 0, 10, 3])
+    y_neg = np.where(y >= V, -1, y)
+    cu = [0, 3, 5, 8]
+    for mode in (L.TOKEN_MEAN, L.SAMPLE_MEAN, L.STABLE):
+        a = L.packed_ce(z, y, cu, mode, 2.5)
+        b = L.packed_ce(z, y_neg, cu, mode, 2.5)
+        assert a[0] == b[0] and np.array_equal(a[1], b[1]) and np.array_equal(a[2], b[2])
+        assert not a[2][1].any() and not a[2][4].any() and a[1][1] == 0.0
+    np.testing.assert_allclose(L.token_weights(y, cu, L.TOKEN_MEAN, vocab=V), np.where(y_neg >= 0, 1 / 5, 0))
+    np.testing.assert_allclose(L.token_weights(y, cu, L.SAMPLE_MEAN, vocab=V),
+                               [1 / 6, 0, 1 / 6, 0, 0, 1 / 9, 1 / 9, 1 / 9])
