@@ -103,6 +103,36 @@ def compare(case: Case, pa, out, q_heads=None, rows=None, cols=None, label=""):
     return res
 
 
+def compare_sample_dense(case: Case, pa, out, sample: int, kv_head: int, label="", threads=8):
+    """Every row and every key column of ONE sample, for one whole kv group (its g query heads), against
+    the matrix-product form of the oracle: O, LSE, dQ, dK, dV to the same bars as compare()."""
+    from oracle.attention_dense import sample_dense
+    a, b = int(pa.cu[sample]), int(pa.cu[sample + 1])
+    q_heads = list(range(kv_head * case.g, (kv_head + 1) * case.g))
+    f32 = lambda w, hs: wl.bf16_bits_to_f32(case.bits(w, pa.T, hs))[a:b]
+    scale = case.scale if case.scale > 0 else None
+    O, LSE, dQ, dK, dV = sample_dense(f32("q", q_heads), f32("k", [kv_head]), f32("v", [kv_head]),
+                                      f32("do", q_heads), scale, rows_per_step=512, threads=threads)
+    g_o = out["o"][a:b][:, q_heads]
+    res = {"o_max": float(np.abs(g_o - O).max()), "o_mean": float(np.abs(g_o - O).mean()),
+           "lse_max": float(np.abs(out["lse"][q_heads][:, a:b] - LSE).max()),
+           "dq_rel": rel_l2(out["dq"][a:b][:, q_heads], dQ),
+           "dk_rel": rel_l2(out["dk"][a:b][:, [kv_head]], dK), "dv_rel": rel_l2(out["dv"][a:b][:, [kv_head]], dV)}
+    # the relative L2 bar again per key tile of 128, so that one bad tile cannot hide in the sample's norm
+    worst = 0.0
+    for t0 in range(0, b - a, 128):
+        sl = slice(t0, min(t0 + 128, b - a))
+        worst = max(worst, rel_l2(out["dk"][a:b][sl][:, [kv_head]], dK[sl]), rel_l2(out["dv"][a:b][sl][:, [kv_head]], dV[sl]),
+                    rel_l2(out["dq"][a:b][sl][:, q_heads], dQ[sl]))
+    res["worst_tile_rel"] = worst
+    print("[parity %s %s] sample %d (%d tokens) kv head %d, all rows and keys: %s" % (
+        case.name, label, sample, b - a, kv_head, " ".join("%s=%.3e" % kv for kv in res.items())), flush=True)
+    assert np.isfinite(list(res.values())).all(), res
+    assert res["o_max"] <= O_MAX and res["o_mean"] <= O_MEAN and res["lse_max"] <= LSE_MAX, res
+    assert max(res["dq_rel"], res["dk_rel"], res["dv_rel"], res["worst_tile_rel"]) <= GRAD_REL, res
+    return res
+
+
 def check_dv_identity(case: Case, pa, dev, out):
     """Holds at any size: rows of P sum to one, so sum_k dV[k,kh] over a sample equals the sum of dO
     over that sample's rows and the group's heads.  Checked on the GPU outputs for every head."""

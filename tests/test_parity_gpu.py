@@ -3,7 +3,7 @@ import numpy as np
 import pytest
 
 import hbp_workloads as wl
-from parity_util import Case, run_gpu, check_plan, compare, check_dv_identity, sampled_rows
+from parity_util import Case, run_gpu, check_plan, compare, compare_sample_dense, check_dv_identity, sampled_rows
 
 pytestmark = pytest.mark.gpu
 
@@ -63,11 +63,28 @@ def test_config3_mixed_32k_sampled():
     check_dv_identity(case, pa, dev, out)
     rng = np.random.default_rng(3)
     rows = sampled_rows(pa.cu, 300, rng)
-    # columns: every key of three short samples, plus the tail of the 16384 sample
+    # Key columns.  Every key of three short samples and of the last sample; in the 16384 sample (key tiles
+    # of 128, taken 32 at a time by the workgroups of a kv head, every second set of 32 in the wrapped block
+    # order) columns in all four sets: tiles 0, 16 (plain order), 32, 48, 63 (wrapped), 64, 95 (plain),
+    # and the tail, 120..127 (wrapped), at tile edges and inside tiles.
     cols = list(range(int(pa.cu[1]), int(pa.cu[3]))) + list(range(int(pa.cu[-2]), int(pa.cu[-1])))
+    cols += [0, 1, 100, 127, 128, 2049, 4095] + list(range(4096, 4101)) + [6207, 8191, 8192, 10000, 12287, 12288]
     cols += list(range(16384 - 160, 16384)) + [16384 - 1000, 16384 - 513]
-    compare(case, pa, out, q_heads=[8, 9, 10, 11], rows=rows, cols=sorted(set(cols)), label="kv-group 2")
+    cols = sorted(set(cols))
+    compare(case, pa, out, q_heads=[8, 9, 10, 11], rows=rows, cols=cols, label="kv-group 2")
     compare(case, pa, out, q_heads=[0, 31], rows=rows[::4], label="first/last head")
+    print("[parity mixed-32k] sampled: %d of %d rows x 4+2 of 32 heads (O, LSE, dQ); %d of %d key columns x 1 of 8 kv "
+          "heads (dK, dV), %d of them in the 16384 sample; sum-of-dV identity on every sample and head"
+          % (len(rows), pa.T, len(cols), pa.T, sum(c < 16384 for c in cols)), flush=True)
+
+
+def test_config3_long_sample_every_row_and_key_of_one_kv_group():
+    """The 16384-token sample of the mixed pack carries 92 % of the pack's attention cost: every row and every
+    key column of it, for one whole kv group (4 query heads), against the matrix-product oracle."""
+    case = Case.from_workload(wl.workload(3))
+    pa, dev, out = run_gpu(case)
+    assert int(pa.cu[1]) == 16384
+    compare_sample_dense(case, pa, out, sample=0, kv_head=5, label="16384 sample")
 
 
 def test_config5_mla_32k_sampled():
@@ -89,11 +106,24 @@ def test_config4_long_128k_sampled():
     pa, dev, out = run_gpu(case)
     check_plan(case, pa)
     check_dv_identity(case, pa, dev, out)
+    print("[parity long-128k] GPU run and sum-of-dV identity done", flush=True)
+    # the 32768 sample: every row and key column of one kv group (8 query heads)
+    compare_sample_dense(case, pa, out, sample=1, kv_head=3, label="32768 sample")
+    # the 98304 sample, kv group 3 (query heads 24..31).  Rows (O, LSE, dQ): sample and tile edges plus random
+    # rows, 512 in all.  Key columns (dK, dV): a run inside key tile 735 (the 22nd set of 32 tiles: plain block
+    # order), runs in tiles 736 and 750 and the sample's last 96 keys (23rd set: wrapped order).  The oracle
+    # needs LSE and D of every row behind the first sampled column, which is what bounds how far down it goes.
     rng = np.random.default_rng(4)
-    rows = sorted(set([0, 1, 127, 128, 98303, 98304, 98305, 131071, 98304 + 4095, 65535, 65536]
-                      + [int(x) for x in rng.integers(0, 131072, 40)]))
-    cols = list(range(98304 - 96, 98304)) + list(range(131072 - 96, 131072)) + [131072 - 300]
-    compare(case, pa, out, q_heads=list(range(24, 32)), rows=rows, cols=sorted(set(cols)), label="kv-group 3")
+    rows = set([0, 1, 31, 32, 127, 128, 255, 256, 4095, 4096, 49151, 49152, 65535, 65536, 98303 - 128, 98302, 98303])
+    rows.update(int(x) for x in rng.integers(0, 98304, 512 - len(rows)))
+    while len(rows) < 512:
+        rows.add(int(rng.integers(0, 98304)))
+    rows = sorted(rows)
+    cols = list(range(94176, 94208)) + list(range(94208, 94224)) + list(range(96000, 96016)) + list(range(98304 - 96, 98304))
+    compare(case, pa, out, q_heads=list(range(24, 32)), rows=rows, cols=cols, label="kv-group 3, 98304 sample")
+    print("[parity long-128k] sampled: 32768 sample whole for 8 of 64 heads; 98304 sample %d of 98304 rows x 8 of 64 "
+          "heads (O, LSE, dQ) and %d of 98304 key columns x 1 of 8 kv heads (dK, dV); sum-of-dV identity on both "
+          "samples and every head" % (len(rows), len(cols)), flush=True)
 
 
 @pytest.mark.parametrize("Hq,Hkv,d,e,pad_h", [(4, 2, 128, 128, 0), (2, 2, 64, 64, 8), (2, 1, 192, 128, 16)])
@@ -227,6 +257,18 @@ def test_long_sample_whose_later_key_tiles_start_below_the_top_and_wrap():
     their query blocks in the wrapped order (start below the sample's last block, skipped blocks last).
     A second, short sample rides along.  dK/dV of every key against the oracle."""
     full(Case([5197, 300], 5497, 8, 8, 64, 64, seed=41, name="wrap"))
+
+
+def test_wrapped_block_order_with_a_group_of_four_heads_at_head_size_128():
+    """The same 41-tile sample at the benchmark's head layout (32 query heads on 8 kv heads, d = 128): key
+    tiles 32..40 take the wrapped order with the four heads of a group innermost.  Every key and row of two
+    kv groups against the oracle, the sum-of-dV identity on all of them."""
+    case = Case([5197, 300], 5497, 32, 8, 128, 128, seed=42, name="wrap-g4")
+    pa, dev, out = run_gpu(case)
+    check_plan(case, pa)
+    check_dv_identity(case, pa, dev, out)
+    compare_sample_dense(case, pa, out, sample=0, kv_head=0, label="group 0", threads=4)
+    compare(case, pa, out, q_heads=[20, 21, 22, 23], label="group 5")
 
 
 @pytest.mark.parametrize("Hq,Hkv", [(8, 1), (12, 3), (8, 8)])
