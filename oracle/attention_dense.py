@@ -17,7 +17,6 @@ library or with ``attn_oracle.c``; it is pinned on its own in ``tests/test_oracl
 """
 from __future__ import annotations
 
-from concurrent.futures import ThreadPoolExecutor
 from typing import Optional
 
 import numpy as np
@@ -57,10 +56,11 @@ def _one_head(qh, kh, vh, doh, scale, rows_per_step):
     return O, LSE, dQ, dK, dV
 
 
-def sample_dense(q, k, v, d_o, scale: Optional[float] = None, rows_per_step: int = 1024, threads: int = 1):
+def sample_dense(q, k, v, d_o, scale: Optional[float] = None, rows_per_step: int = 512):
     """One sample, any number of kv groups.  q [s,Hq,d], k [s,Hkv,d], v [s,Hkv,e], d_o [s,Hq,e].
     Returns O [s,Hq,e], LSE [Hq,s], dQ [s,Hq,d], dK [s,Hkv,d], dV [s,Hkv,e], all float64.
-    threads: query heads worked on at a time (each holds a few [rows_per_step, s] matrices)."""
+    The heads are taken one after the other from this one thread (the BLAS underneath may use every core:
+    calling a multi-threaded BLAS from several Python threads at once gave wrong products on some hosts)."""
     s, Hq, d = q.shape
     Hkv, e = k.shape[1], v.shape[2]
     assert Hq % Hkv == 0 and k.shape == (s, Hkv, d) and v.shape == (s, Hkv, e) and d_o.shape == (s, Hq, e)
@@ -71,15 +71,7 @@ def sample_dense(q, k, v, d_o, scale: Optional[float] = None, rows_per_step: int
     def work(h):
         return _one_head(f64(q, h), f64(k, h // g), f64(v, h // g), f64(d_o, h), sc, rows_per_step)
 
-    if threads > 1:
-        # the heads run side by side; the BLAS underneath gets the remaining share of the cores
-        import os
-        from threadpoolctl import threadpool_limits
-        with threadpool_limits(limits=max(1, len(os.sched_getaffinity(0)) // threads)):
-            with ThreadPoolExecutor(max_workers=threads) as ex:
-                res = list(ex.map(work, range(Hq)))
-    else:
-        res = [work(h) for h in range(Hq)]
+    res = [work(h) for h in range(Hq)]
     O = np.stack([r[0] for r in res], axis=1)
     LSE = np.stack([r[1] for r in res], axis=0)
     dQ = np.stack([r[2] for r in res], axis=1)

@@ -103,7 +103,7 @@ def compare(case: Case, pa, out, q_heads=None, rows=None, cols=None, label=""):
     return res
 
 
-def compare_sample_dense(case: Case, pa, out, sample: int, kv_head: int, label="", threads=8):
+def compare_sample_dense(case: Case, pa, out, sample: int, kv_head: int, label=""):
     """Every row and every key column of ONE sample, for one whole kv group (its g query heads), against
     the matrix-product form of the oracle: O, LSE, dQ, dK, dV to the same bars as compare()."""
     from oracle.attention_dense import sample_dense
@@ -112,7 +112,7 @@ def compare_sample_dense(case: Case, pa, out, sample: int, kv_head: int, label="
     f32 = lambda w, hs: wl.bf16_bits_to_f32(case.bits(w, pa.T, hs))[a:b]
     scale = case.scale if case.scale > 0 else None
     O, LSE, dQ, dK, dV = sample_dense(f32("q", q_heads), f32("k", [kv_head]), f32("v", [kv_head]),
-                                      f32("do", q_heads), scale, rows_per_step=512, threads=threads)
+                                      f32("do", q_heads), scale, rows_per_step=512)
     g_o = out["o"][a:b][:, q_heads]
     res = {"o_max": float(np.abs(g_o - O).max()), "o_mean": float(np.abs(g_o - O).mean()),
            "lse_max": float(np.abs(out["lse"][q_heads][:, a:b] - LSE).max()),

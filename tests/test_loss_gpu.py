@@ -128,8 +128,12 @@ def test_large_logits_and_out_of_range_label_is_ignored():
     a = run_gpu(bits, y2, cu, 0)
     b = run_gpu(bits, y3, cu, 0)
     assert a[0] == b[0] and np.array_equal(a[1], b[1]) and np.array_equal(a[2], b[2])
-    for mode in (0, 1, 2):                           # the oracle takes the same reading of such a label
-        check(bits, y2, cu, mode, 3.0)
+    # the oracle takes the same reading of such a label: all three normalisers on ordinary logits
+    bits, y, cu = make_case([9, 17], 2048, 6, p_mask=0.2)
+    y[3] = 2048
+    y[20] = 5000
+    for mode in (0, 1, 2):
+        check(bits, y, cu, mode, 3.0)
 
 
 def test_loss_is_bit_stable_and_gradient_optional():

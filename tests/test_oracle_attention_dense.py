@@ -31,7 +31,7 @@ def torch_reference(q, k, v, d_o, scale):
 def test_matches_autograd_of_the_dense_definition(s, Hq, Hkv, d, e, step):
     q, k, v, d_o = make(s, Hq, Hkv, d, e, seed=11)
     scale = 0.37
-    got = sample_dense(q, k, v, d_o, scale, rows_per_step=step, threads=2)
+    got = sample_dense(q, k, v, d_o, scale, rows_per_step=step)
     want = torch_reference(q, k, v, d_o, scale)
     for a, b, name in zip(got, want, ("O", "LSE", "dQ", "dK", "dV")):
         assert np.abs(a - b).max() < 1e-11, name

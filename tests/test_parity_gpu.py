@@ -267,7 +267,7 @@ def test_wrapped_block_order_with_a_group_of_four_heads_at_head_size_128():
     pa, dev, out = run_gpu(case)
     check_plan(case, pa)
     check_dv_identity(case, pa, dev, out)
-    compare_sample_dense(case, pa, out, sample=0, kv_head=0, label="group 0", threads=4)
+    compare_sample_dense(case, pa, out, sample=0, kv_head=0, label="group 0")
     compare(case, pa, out, q_heads=[20, 21, 22, 23], label="group 5")
 
 
