@@ -1,6 +1,6 @@
 """Oracle of the Hierarchical Groups Auto-Selection (test infrastructure only).
 
-Plain Python, the paper's steps in the paper's order:
+Plain Python.  What each routine computes, as the paper defines it:
 
 * GreedyProfileCkpt (appendix "Implementation Details of Hierarchical Groups Auto-Selection",
   GreedyProfileCkpt algorithm): profile the REMAINING memory with c_min and with c_max checkpointed
@@ -33,59 +33,55 @@ from typing import Callable, List, Optional, Sequence, Tuple
 
 
 def greedy_profile_ckpt(l: int, sp: int, c_min: int, c_max: int, profile_memory: Callable) -> Optional[int]:
+    """Fewest checkpointed layers that still fit, from a line through two memory probes.  Remaining memory
+    is modelled as m(c) = m2 - m_ave (c_max - c); the answer is the smallest whole c >= 0 with m(c) >= 0."""
     if not (0 <= c_min < c_max):
         raise ValueError("need 0 <= c_min < c_max")
-    m1 = profile_memory(l, sp, c_min)
-    m2 = profile_memory(l, sp, c_max)
-    if m2 < 0:
+    m1, m2 = profile_memory(l, sp, c_min), profile_memory(l, sp, c_max)
+    if m2 < 0:                                   # does not fit even with c_max layers checkpointed
         return None
-    m_ave = (m2 - m1) / (c_max - c_min)
-    if m_ave > 0:
-        c_o = c_max - m2 / m_ave
-        return max(0, math.ceil(c_o))
-    return 0 if m2 - m_ave * c_max >= 0 else None
+    m_ave = (m2 - m1) / (c_max - c_min)          # memory freed per checkpointed layer
+    if m_ave <= 0:                               # checkpointing frees nothing: all or nothing at c = 0
+        return 0 if m2 - m_ave * c_max >= 0 else None
+    return max(0, math.ceil(c_max - m2 / m_ave))  # zero crossing of the line, as a layer count
 
 
 def find_best_sp_ckpt(l: int, sp_set: Sequence[int], c_min: int, c_max: int, profile_memory: Callable,
                       profile_time: Callable) -> Optional[Tuple[int, int, float]]:
-    p: List[float] = []
-    o: List[Tuple[int, int]] = []
-    for sp in sp_set:
+    """argmin of the profiled iteration time over the feasible (sp, ckpt) pairs of length l, ckpt being
+    GreedyProfileCkpt's layer count for that sp; the first of equal minima wins.  None: nothing fits."""
+    feasible = []
+    for position, sp in enumerate(sp_set):
         ckpt = greedy_profile_ckpt(l, sp, c_min, c_max, profile_memory)
-        if ckpt is None:
-            continue
-        t = profile_time(l, sp, ckpt)
-        if t is None or not (t < math.inf):
-            continue
-        p.append(t)
-        o.append((sp, ckpt))
-    if not p:
+        t = None if ckpt is None else profile_time(l, sp, ckpt)
+        if t is not None and t < math.inf:
+            feasible.append((t, position, sp, ckpt))
+    if not feasible:
         return None
-    j = p.index(min(p))
-    return o[j][0], o[j][1], p[j]
+    t, _, sp, ckpt = min(feasible)
+    return sp, ckpt, t
 
 
 def stage2(lengths: Sequence[int], strategies: Sequence[Optional[Tuple[int, int]]], times: Sequence[float]):
-    """Stage 2 of Algorithm 1 from the per-length results of Stage 1.  Returns (groups, sp, ckpt, j)."""
+    """Stage 2 of Algorithm 1 from the per-length results of Stage 1.  Returns (groups, sp, ckpt, j).
+
+    The groups are the set {l_1, l_best, l_max}, plus l_2 when it lies above l_best, in ascending order,
+    with l_1 = floor(l_best / sp_best) and l_2 = floor(l_max / sp_max).  l_best and l_max train with their
+    own Stage 1 strategy; a derived length trains with SP 1 and the layer count of the strategy it comes
+    from, unless it coincides with l_best or l_max."""
     if strategies[-1] is None:
         raise ValueError("the longest length has no feasible strategy")
-    finite = [t if strategies[i] is not None else math.inf for i, t in enumerate(times)]
-    j = finite.index(min(finite))
-    s_best, l_best = strategies[j], lengths[j]
-    s_max, l_max = strategies[-1], lengths[-1]
-    l_1 = l_best // s_best[0]
-    l_2 = l_max // s_max[0]
+    j = min((i for i in range(len(lengths)) if strategies[i] is not None), key=lambda i: (times[i], i))
+    (sp_best, ckpt_best), l_best = strategies[j], lengths[j]
+    (sp_max, ckpt_max), l_max = strategies[-1], lengths[-1]
+    l_1, l_2 = l_best // sp_best, l_max // sp_max
+    plan = {l_1: (1, ckpt_best)}
     if l_2 > l_best:
-        l_p = [(l_1, 1, s_best[1]), (l_best, s_best[0], s_best[1]), (l_2, 1, s_max[1]), (l_max, s_max[0], s_max[1])]
-    else:
-        l_p = [(l_1, 1, s_best[1]), (l_best, s_best[0], s_best[1]), (l_max, s_max[0], s_max[1])]
-    out = []
-    for g in l_p:  # a repeated length keeps its LAST entry (the length's own strategy)
-        if out and out[-1][0] == g[0]:
-            out[-1] = g
-        else:
-            out.append(g)
-    return [g[0] for g in out], [g[1] for g in out], [g[2] for g in out], j
+        plan[l_2] = (1, ckpt_max)
+    plan[l_best] = (sp_best, ckpt_best)
+    plan[l_max] = (sp_max, ckpt_max)
+    groups = sorted(plan)
+    return groups, [plan[l][0] for l in groups], [plan[l][1] for l in groups], j
 
 
 def auto_selection(lengths: Sequence[int], sp_set: Sequence[int], c_min: int, c_max: int,

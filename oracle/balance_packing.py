@@ -1,6 +1,6 @@
 """Oracle of the multi-level Balance Packing planner (test infrastructure only).
 
-Plain Python integers and lists, every step written as the paper states it, in the paper's order:
+Plain Python integers and lists.  What each step computes, as the paper defines it:
 
 * GroupData (Appendix "Implementation Details of Balance Packing", GroupData function):
   sample x goes to group D_i when len(x) lies in (l_{i-1}, l_i], l_0 = 0.
@@ -79,24 +79,39 @@ def packing_ffd(items: Sequence[int], lengths: Sequence[int], cap: int) -> List[
     return packs
 
 
+def take_what_fits(pool: List[int], room: int, lengths: Sequence[int]):
+    """One pass over `pool` in its order with `room` tokens of space: a sample is taken when it fits the
+    space that is left at the moment it is looked at.  Returns (taken, left over, space left)."""
+    taken, left = [], []
+    for x in pool:
+        if lengths[x] <= room:
+            taken.append(x)
+            room -= lengths[x]
+        else:
+            left.append(x)
+    return taken, left, room
+
+
 def greedy_fill(packs: List[List[int]], cap: int, smaller: List[List[int]], lengths: Sequence[int]) -> None:
-    """GreedyFill(G_i, l_i, [D_{i-1}, ..., D_1]); `smaller` is given in that order and is edited in place."""
+    """GreedyFill(G_i, l_i, [D_{i-1}, ..., D_1]): the residual space of every pack of level i is offered to
+    the smaller groups, the nearest group first; the packs are served in creation order and a sample that
+    went into a pack is gone from its group.  `smaller` is given nearest first and is edited in place."""
     for g in packs:
-        for d in smaller:
-            keep = []
-            for x in d:
-                if sum(lengths[s] for s in g) + lengths[x] <= cap:
-                    g.append(x)
-                else:
-                    keep.append(x)
-            d[:] = keep
+        room = cap - sum(lengths[s] for s in g)
+        for level, pool in enumerate(smaller):
+            taken, smaller[level][:], room = take_what_fits(pool, room, lengths)
+            g.extend(taken)
+
+
+def attention_complexity(pack: Sequence[int], lengths: Sequence[int]) -> int:
+    """a = sum of len(x)^2 over the samples of a pack (Section 3.1; Attention Balance Sort)."""
+    return sum(lengths[x] * lengths[x] for x in pack)
 
 
 def attention_balance_sort(packs: List[List[int]], lengths: Sequence[int]) -> List[List[int]]:
-    """Sort the packs of one level by attention complexity a = sum len^2 (descending, stable)."""
-    a = [sum(lengths[x] * lengths[x] for x in g) for g in packs]
-    order = sorted(range(len(packs)), key=lambda p: (-a[p], p))
-    return [packs[p] for p in order]
+    """The packs of one level ordered by attention complexity, largest first; equal ones keep their
+    creation order (Python's sort is stable)."""
+    return sorted(packs, key=lambda g: -attention_complexity(g, lengths))
 
 
 def balance_packing(lengths: Sequence[int], group_lens: Sequence[int], packs_per_batch: Sequence[int],
@@ -145,7 +160,7 @@ def metrics(batches: List[Dict], lengths: Sequence[int], group_lens: Sequence[in
     for b in batches:
         i = b["level"]
         tokens = [sum(lengths[x] for x in g) for g in b["packs"]]
-        attn = [sum(lengths[x] * lengths[x] for x in g) for g in b["packs"]]
+        attn = [attention_complexity(g, lengths) for g in b["packs"]]
         if len(b["packs"]) == packs_per_batch[i]:
             dbr += ratio_to_max(tokens)
             abr += ratio_to_max(attn)
