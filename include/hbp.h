@@ -39,7 +39,9 @@ enum {
   HBP_ERR_CAPACITY = 4,    /* an output array of the planner is too small                */
   HBP_ERR_WORKSPACE = 5,   /* workspace missing, misaligned or smaller than required     */
   HBP_ERR_DEVICE = 6,      /* the HIP runtime refused the launch (hipGetLastError)       */
-  HBP_ERR_NO_MEMORY = 7    /* a host planner could not allocate its working memory       */
+  HBP_ERR_NO_MEMORY = 7,   /* a host planner could not allocate its working memory       */
+  HBP_ERR_STATIC_LIMIT = 8 /* hbp_varlen_attn_bwd_static: the problem needs more scratch
+                            * than HBP_STATIC_SCRATCH_BYTES                               */
 };
 
 /* Static, never-freed description of a status code. */
@@ -191,6 +193,37 @@ hbp_status hbp_varlen_attn_bwd(const hbp_attn_desc* desc, const void* q, const v
                                void* workspace, size_t workspace_bytes,
                                hbp_profile_rec* profile_or_null, hbp_profile_rec* profile_dq_or_null,
                                void* stream);
+
+/*
+ * hbp_varlen_attn_bwd_static — the backward above for callers that cannot allocate device memory and
+ * have no workspace to hand over: code under HIP graph capture, tight serving or training loops,
+ * harnesses that forbid hipMalloc.  Same arguments minus the workspace, same kernels, same results
+ * bit for bit.  The scratch (queue counters, D, LSE*log2e and, with fewer than 8 kv heads, the partial
+ * sums of dK and dV) lives in a static device array of HBP_STATIC_SCRATCH_BYTES inside the library: each
+ * GPU the library runs on holds that much from the moment the library's code is loaded there until
+ * the process ends.  The call allocates and frees nothing; the first call on a device looks up the
+ * array's address there (make that first call outside a graph capture).
+ * Limit: hbp_workspace_bytes(desc, HBP_BWD) must not exceed HBP_STATIC_SCRATCH_BYTES, else
+ * HBP_ERR_STATIC_LIMIT and nothing is launched (64 MiB holds n_q_heads * total_tokens up to 8 Mi rows,
+ * e.g. 64 heads x 131072 tokens, with 8 or more kv heads).
+ * Every call on a GPU uses that GPU's one array: calls that may overlap in time on one GPU (different
+ * streams, different host threads) race on it and must be serialised by the caller; calls that follow
+ * each other on one stream are safe.  Nothing in the array has to start at zero and nothing is read
+ * before this call has written it (the pre-pass resets the counters and fills D and LSE*log2e; the
+ * partial sums are written by the key-tile kernel before the reduce kernel reads them), so what an
+ * earlier, larger call left behind is never seen.
+ * Errors: as hbp_varlen_attn_bwd without HBP_ERR_WORKSPACE, plus HBP_ERR_STATIC_LIMIT, and
+ * HBP_ERR_DEVICE when the array's address cannot be obtained.
+ */
+#define HBP_STATIC_SCRATCH_BYTES ((size_t)((64u << 20) + 4096u))
+hbp_status hbp_varlen_attn_bwd_static(const hbp_attn_desc* desc, const void* q, const void* k,
+                                      const void* v, const void* o, const float* lse, const void* d_o,
+                                      const int32_t* cu_seqlens,
+                                      const hbp_tile* q_tiles, int32_t n_q_tiles,
+                                      const hbp_tile* kv_tiles, int32_t n_kv_tiles,
+                                      void* dq, void* dk, void* dv,
+                                      hbp_profile_rec* profile_or_null, hbp_profile_rec* profile_dq_or_null,
+                                      void* stream);
 
 /*
  * hbp_set_kernel_events — measurement hook.  When both events are non-NULL, every later call of

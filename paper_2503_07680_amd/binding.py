@@ -15,7 +15,7 @@ HBP_FWD, HBP_BWD, HBP_BWD_DQ = 0, 1, 2
 HBP_TILES_QUERY, HBP_TILES_KEY = 0, 1
 
 EXPORTED_SYMBOLS = ["hbp_status_string", "hbp_pack_plan", "hbp_tile_rows", "hbp_fwd_tile_rows", "hbp_workspace_bytes",
-                    "hbp_profile_capacity", "hbp_varlen_attn_fwd", "hbp_varlen_attn_bwd",
+                    "hbp_profile_capacity", "hbp_varlen_attn_fwd", "hbp_varlen_attn_bwd", "hbp_varlen_attn_bwd_static",
                     "hbp_set_kernel_events", "hbp_mfma_probe", "hbp_balance_packing",
                     "hbp_packed_ce_workspace_bytes", "hbp_packed_ce", "hbp_auto_select"]
 
@@ -102,6 +102,9 @@ def load_library():
     lib.hbp_varlen_attn_bwd.restype = i32
     lib.hbp_varlen_attn_bwd.argtypes = [descp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, i32, vp, vp, vp, vp,
                                         ctypes.c_size_t, vp, vp, vp]
+    lib.hbp_varlen_attn_bwd_static.restype = i32
+    lib.hbp_varlen_attn_bwd_static.argtypes = [descp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, i32, vp, vp, vp,
+                                               vp, vp, vp]
     lib.hbp_set_kernel_events.restype = i32
     lib.hbp_set_kernel_events.argtypes = [i32, vp, vp]
     lib.hbp_balance_packing.restype = i32
@@ -279,6 +282,22 @@ def hbp_varlen_attn_bwd(desc: AttnDesc, q, k, v, o, lse, d_o, cu_seqlens, q_tile
         stream)
     if st != 0:
         raise HbpError(st, "hbp_varlen_attn_bwd")
+
+
+HBP_STATIC_SCRATCH_BYTES = (64 << 20) + 4096
+HBP_ERR_STATIC_LIMIT = 8
+
+
+def hbp_varlen_attn_bwd_static(desc: AttnDesc, q, k, v, o, lse, d_o, cu_seqlens, q_tiles, n_q_tiles: int,
+                               kv_tiles, n_kv_tiles: int, dq, dk, dv, profile=None, profile_dq=None,
+                               stream: Optional[int] = None) -> None:
+    """The backward with the library's static scratch array in place of a workspace (allocates nothing)."""
+    st = load_library().hbp_varlen_attn_bwd_static(
+        ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(d_o), _ptr(cu_seqlens),
+        _ptr(q_tiles), int(n_q_tiles), _ptr(kv_tiles), int(n_kv_tiles), _ptr(dq), _ptr(dk), _ptr(dv),
+        _ptr(profile), _ptr(profile_dq), stream)
+    if st != 0:
+        raise HbpError(st, "hbp_varlen_attn_bwd_static")
 
 
 HBP_LOSS_TOKEN_MEAN, HBP_LOSS_SAMPLE_MEAN, HBP_LOSS_STABLE = 0, 1, 2

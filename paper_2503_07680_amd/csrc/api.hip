@@ -2,6 +2,7 @@
 #include <climits>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 
 #include "common.hpp"
 
@@ -103,6 +104,7 @@ extern "C" const char* hbp_status_string(hbp_status s) {
     case HBP_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case HBP_ERR_DEVICE: return "HIP runtime error at launch";
     case HBP_ERR_NO_MEMORY: return "out of host memory";
+    case HBP_ERR_STATIC_LIMIT: return "problem needs more scratch than the library's static buffer holds";
     default: return "unknown status";
   }
 }
@@ -295,14 +297,38 @@ extern "C" hbp_status hbp_varlen_attn_fwd(const hbp_attn_desc* desc, const void*
   return HBP_OK;
 }
 
-extern "C" hbp_status hbp_varlen_attn_bwd(const hbp_attn_desc* desc, const void* q, const void* k,
-                                          const void* v, const void* o, const float* lse,
-                                          const void* d_o, const int32_t* cu_seqlens,
-                                          const hbp_tile* q_tiles, int32_t n_q_tiles,
-                                          const hbp_tile* kv_tiles, int32_t n_kv_tiles, void* dq,
-                                          void* dk, void* dv, void* workspace,
-                                          size_t workspace_bytes, hbp_profile_rec* profile,
-                                          hbp_profile_rec* profile_dq, void* stream) {
+namespace {
+
+// Scratch of the entry point that takes no workspace: one array per GPU, held from the moment the
+// library's code is loaded on that GPU until the process ends.  In host code this name is only a
+// handle for hipGetSymbolAddress; the device address is looked up once per device (static_scratch).
+constexpr size_t kStaticScratchBytes = HBP_STATIC_SCRATCH_BYTES;  // 64 MiB of per-row scalars + counters
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device (each GPU has its own copy at its own address).
+hbp_status static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return HBP_ERR_DEVICE;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return HBP_ERR_DEVICE;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return HBP_OK;
+}
+
+// Shared by both backward entry points.  use_static: the workspace is the library's static array.
+hbp_status bwd_impl(const hbp_attn_desc* desc, const void* q, const void* k, const void* v, const void* o,
+                    const float* lse, const void* d_o, const int32_t* cu_seqlens, const hbp_tile* q_tiles,
+                    int32_t n_q_tiles, const hbp_tile* kv_tiles, int32_t n_kv_tiles, void* dq, void* dk, void* dv,
+                    void* workspace, size_t workspace_bytes, bool use_static, hbp_profile_rec* profile,
+                    hbp_profile_rec* profile_dq, void* stream) {
   Strides st;
   const hbp_status s = check_desc(desc, &st);
   if (s != HBP_OK) return s;
@@ -310,8 +336,11 @@ extern "C" hbp_status hbp_varlen_attn_bwd(const hbp_attn_desc* desc, const void*
   if (!item_count_fits(n_q_tiles, desc->n_q_heads) || !item_count_fits(n_kv_tiles, desc->n_q_heads))
     return HBP_ERR_INVALID_ARG;
   const BwdLayout lay = bwd_layout(desc);
-  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < lay.total)
+  if (use_static) {
+    if (lay.total > kStaticScratchBytes) return HBP_ERR_STATIC_LIMIT;
+  } else if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < lay.total) {
     return HBP_ERR_WORKSPACE;
+  }
   if (desc->total_tokens == 0) return HBP_OK;
   if (!q || !k || !v || !o || !lse || !d_o || !cu_seqlens || !dq || !dk || !dv) return HBP_ERR_INVALID_ARG;
   if ((n_kv_tiles > 0 && !kv_tiles) || (n_q_tiles > 0 && !q_tiles)) return HBP_ERR_INVALID_ARG;
@@ -330,6 +359,10 @@ extern "C" hbp_status hbp_varlen_attn_bwd(const hbp_attn_desc* desc, const void*
   p.dq = static_cast<uint16_t*>(dq);
   p.dk = static_cast<uint16_t*>(dk);
   p.dv = static_cast<uint16_t*>(dv);
+  if (use_static) {
+    const hbp_status ss = static_scratch(&workspace);
+    if (ss != HBP_OK) return ss;
+  }
   char* ws = static_cast<char*>(workspace);
   p.counter = reinterpret_cast<int32_t*>(ws);
   p.counter_dq = reinterpret_cast<int32_t*>(ws + 1024);
@@ -362,4 +395,29 @@ extern "C" hbp_status hbp_varlen_attn_bwd(const hbp_attn_desc* desc, const void*
   if (hbp::launch_bwd(desc->d_qk, desc->d_v, p, grid_dq, grid_dkdv, static_cast<hipStream_t>(stream), ev) != 0)
     return HBP_ERR_DEVICE;
   return HBP_OK;
+}
+
+}  // namespace
+
+extern "C" hbp_status hbp_varlen_attn_bwd(const hbp_attn_desc* desc, const void* q, const void* k,
+                                          const void* v, const void* o, const float* lse,
+                                          const void* d_o, const int32_t* cu_seqlens,
+                                          const hbp_tile* q_tiles, int32_t n_q_tiles,
+                                          const hbp_tile* kv_tiles, int32_t n_kv_tiles, void* dq,
+                                          void* dk, void* dv, void* workspace,
+                                          size_t workspace_bytes, hbp_profile_rec* profile,
+                                          hbp_profile_rec* profile_dq, void* stream) {
+  return bwd_impl(desc, q, k, v, o, lse, d_o, cu_seqlens, q_tiles, n_q_tiles, kv_tiles, n_kv_tiles, dq, dk, dv,
+                  workspace, workspace_bytes, false, profile, profile_dq, stream);
+}
+
+extern "C" hbp_status hbp_varlen_attn_bwd_static(const hbp_attn_desc* desc, const void* q, const void* k,
+                                                 const void* v, const void* o, const float* lse,
+                                                 const void* d_o, const int32_t* cu_seqlens,
+                                                 const hbp_tile* q_tiles, int32_t n_q_tiles,
+                                                 const hbp_tile* kv_tiles, int32_t n_kv_tiles, void* dq,
+                                                 void* dk, void* dv, hbp_profile_rec* profile,
+                                                 hbp_profile_rec* profile_dq, void* stream) {
+  return bwd_impl(desc, q, k, v, o, lse, d_o, cu_seqlens, q_tiles, n_q_tiles, kv_tiles, n_kv_tiles, dq, dk, dv,
+                  nullptr, 0, true, profile, profile_dq, stream);
 }
