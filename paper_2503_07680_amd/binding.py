@@ -75,10 +75,15 @@ def library_path() -> str:
 
 
 def load_library():
-    """Load libhbp.so; raises if it has not been built (no fallback path exists)."""
-    global _lib
+    """Load libhbp.so; raises if it has not been built (no fallback path exists).  The environment
+    variable HBP_LIBRARY names another build of the same library to load instead (the race-hunting
+    build libhbp_racehunt.so, say); it is read once, at the first call."""
+    global _lib, _LIB_PATH
     if _lib is not None:
         return _lib
+    override = os.environ.get("HBP_LIBRARY")
+    if override:
+        _LIB_PATH = override if os.path.isabs(override) else os.path.join(_PKG, override)
     if not os.path.exists(_LIB_PATH):
         raise FileNotFoundError(
             "%s not found: build it with `python -m paper_2503_07680_amd.build`" % _LIB_PATH)

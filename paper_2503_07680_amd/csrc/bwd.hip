@@ -238,6 +238,7 @@ __global__ __launch_bounds__(kThreads, DQK <= 128 ? 2 : 1) void bwd_dq_kernel(co
         cur_buf = buf;
       };
       auto begin_tile = [&](int kt) {
+        race_fence();
         wait_async_loads();
         __syncthreads();
         if (kt + 1 < nkt) issue(kt + 1);
@@ -701,10 +702,12 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
         __syncthreads();
         if (step + 1 < n_steps) issue_next(1);
         do_step(step, std::integral_constant<int, 0>{});
+        race_fence();
         wait_async_loads();
         __syncthreads();
         if (step + 2 < n_steps) issue_next(0);
         do_step(step + 1, std::integral_constant<int, 1>{});
+        race_fence();
       }
 
       if (p.n_split == 1) {

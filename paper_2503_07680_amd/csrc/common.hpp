@@ -397,6 +397,19 @@ __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// Race-hunting build (-DHBP_RACE_HUNT, a second library next to the release one): a full fence of the
+// workgroup - this wave's tile copies and LDS operations complete, then a barrier - at the end of every
+// phase of the forward and of every tile or step of the backward kernels.  The release build gets by with
+// one barrier per tile and relies on which buffer each phase still reads; if that reasoning were wrong
+// somewhere, the two builds would differ.  The arithmetic and its order are the same, so they must agree
+// bit for bit.  Every call site is reached by all wavefronts of the workgroup equally often.
+__device__ __forceinline__ void race_fence() {
+#ifdef HBP_RACE_HUNT
+  wait_async_loads();
+  __syncthreads();
+#endif
+}
+
 // Workgroup-wide fetch of the next item: thread 0 takes it, everybody reads it back as scalars.
 // slot: two ints of LDS that nobody else touches between the surrounding barriers.
 __device__ __forceinline__ bool next_item(const WorkQueues& wq, int* slot, int tid, int& q_cur, int& q_tried,

@@ -414,13 +414,16 @@ __global__ __launch_bounds__(kThreads * HP * TP, 2 / (HP * TP)) void fwd_kernel(
       int t = 0;
       if (nkt > 0) {
         w.template any_phase<0>(0, nb);
+        race_fence();
         tile_barrier(0);
         w.preload_k(0);
         w.template any_phase<1>(1, nb);
+        race_fence();
         t = 1;
       }
       for (; t < t_hot_end; ++t) {
         w.template phase<0, true>(64 * t + 32, typename W::Parts{}, [](int) {});
+        race_fence();
         tile_sync(t);
         w.preload_k(0);
         // the copies of K(t+2) and V(t+1) go out one at a time behind this phase's MFMAs (a burst
@@ -444,12 +447,15 @@ __global__ __launch_bounds__(kThreads * HP * TP, 2 / (HP * TP)) void fwd_kernel(
             }
           }
         });
+        race_fence();
       }
       for (; t < nkt; ++t) {
         w.template any_phase<0>(2 * t, nb);
+        race_fence();
         tile_barrier(t);
         w.preload_k(0);
         w.template any_phase<1>(2 * t + 1, nb);
+        race_fence();
       }
       // B of the last block when the wave's blocks fill every tile: V(nkt-1) is still in LDS and
       // the offsets already point at it
