@@ -23,10 +23,38 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA (published)
 
-# HBM bytes of one launch of the dominant kernel (backward key-tile kernel) on workload 3, from the two
-# rocprofv3 counter runs summarised in profiles/hbm_traffic_mixed32k.md:
-# FETCH_SIZE 1 540 810 KiB x 2.0 (calibration factor) + WRITE_SIZE 131 623 KiB x 1.0.
-DKDV_TRAFFIC_BYTES = {3: int((1540810 * 2.0 + 131623 * 1.0) * 1024)}
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic_table.md")
+DOMINANT_KERNEL_SOURCES = ("bwd.hip", "common.hpp")   # what the backward key-tile kernel is compiled from
+
+
+def kernel_sources_digest() -> str:
+    """First 12 hex digits of the SHA-256 over the dominant kernel's source files: the key that ties a
+    measured traffic figure to the build it was measured on."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in DOMINANT_KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2503_07680_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:12]
+
+
+def measured_traffic_bytes(config: int, seed: int):
+    """HBM bytes of one launch of the dominant kernel from the rocprofv3 counter runs recorded in
+    profiles/hbm_traffic_table.md (FETCH_SIZE and WRITE_SIZE in KiB per dispatch, each with its calibration
+    factor), or None when the table has no row for this workload, seed and kernel source digest."""
+    digest = kernel_sources_digest()
+    try:
+        lines = open(TRAFFIC_TABLE).read().splitlines()
+    except OSError:
+        return None
+    for line in lines:
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) != 7 or not cells[0].isdigit():
+            continue
+        cfg, sd, dig, fetch_kib, fetch_x, write_kib, write_x = cells
+        if int(cfg) == config and int(sd) == seed and dig == digest:
+            return int((float(fetch_kib) * float(fetch_x) + float(write_kib) * float(write_x)) * 1024)
+    return None
 
 
 class HipEvents:
@@ -112,7 +140,8 @@ def cpu_baseline(w, cu, target_pairs=2.0e8):
     flops = len(q_heads) * pairs * (2 * (w.d_qk + w.d_v) + 2 * (3 * w.d_qk + 2 * w.d_v))
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.oracle_threads(),
             "kind": "oracle", "seconds": dt, "cpu_model": cpu_model(),
-            "sample": "%s (%d tokens, %d causal pairs), %d query heads / %d kv heads, fwd+bwd in fp64"
+            "sample": "%s (%d tokens, %d causal pairs), %d query heads / %d kv heads, fwd+bwd in fp64; a sub-pack "
+                      "sized for 10-30 s of oracle time, not the subset the parity tests compare"
                       % (what, int(sum(sub_lens)), pairs, len(q_heads), len(kv_heads))}
 
 
@@ -389,7 +418,9 @@ def main():
                      "achieved": bwd_tf, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": bwd_tf / PEAK_BF16_TFLOPS,
                      "sustained_mfma_only_tflops": sustained_tf, "frac_of_sustained": bwd_tf / sustained_tf,
-                     "traffic": DKDV_TRAFFIC_BYTES.get(args.config) if args.seed == 0 else None},
+                     "traffic": None if (args.heads or args.row_pad) else measured_traffic_bytes(args.config, args.seed),
+                     "traffic_key": {"config": args.config, "seed": args.seed, "kernel_sources_sha256_12": kernel_sources_digest(),
+                                     "table": "profiles/hbm_traffic_table.md"}},
         "busy_time_spread": {"fwd": spread_f, "bwd_dkdv": spread_b, "bwd_dq": spread_q},
     }
     if graph_info:
