@@ -252,6 +252,27 @@ def test_seeded_sweep_of_random_packs():
                   scale=scale, name="sweep-%d" % i))
 
 
+def test_seeded_sweep_of_larger_packs():
+    """Ten seeded packs whose samples span many tiles (up to 2500 tokens: the unmasked hot loops of all three
+    kernels, several query blocks per key tile, GQA groups of 1 to 8), with short samples in between and all
+    three head sizes.  Every output of every head against the oracle, plus the plan and the dV identity."""
+    rng = np.random.default_rng(4048)
+    dims = [(128, 128), (64, 64), (192, 128)]
+    for i in range(10):
+        lengths = [int(rng.integers(600, 2500)) for _ in range(int(rng.integers(1, 3)))]
+        lengths += [int(rng.integers(1, 300)) for _ in range(int(rng.integers(0, 5)))]
+        order = rng.permutation(len(lengths))
+        lengths = [lengths[j] for j in order]
+        total = sum(lengths)
+        pack_len = total if i % 2 else total - int(rng.integers(0, 100))
+        Hkv = int(rng.choice([1, 2, 8]))
+        g = int(rng.choice([1, 2, 4, 8])) if Hkv < 8 else int(rng.choice([1, 2]))
+        d, e = dims[i % 3]
+        print("larger sweep case", i, lengths, pack_len, Hkv * g, Hkv, d, e, flush=True)
+        full(Case(lengths, pack_len, Hkv * g, Hkv, d, e, seed=300 + i, sigma=float(rng.choice([0.5, 1.0])),
+                  name="sweep-large-%d" % i))
+
+
 def test_long_sample_whose_later_key_tiles_start_below_the_top_and_wrap():
     """41 key tiles of one sample on 8 kv heads: 32 workgroups share a kv head, so key tiles 32..40 take
     their query blocks in the wrapped order (start below the sample's last block, skipped blocks last).
