@@ -42,6 +42,30 @@ def test_explicit_scale_and_small_sigma():
     full(Case([190, 66], 256, 4, 4, 64, 64, seed=26, sigma=0.5, scale=0.2, name="scale"))
 
 
+def test_peaked_softmax_with_large_logits():
+    """Scores with a standard deviation of about 18 (Q, K drawn with sigma 4, scale 1/sqrt(d)): every row's
+    softmax is dominated by a few keys, the running maximum moves often (the lazy rescale takes its slow
+    path) and most probabilities underflow.  Relative bars on every tensor (the absolute bars on O are for
+    values of unit scale), LSE to 1e-3 relative to its size."""
+    import oracle
+    from parity_util import rel_l2
+    case = Case([700, 129, 33, 1, 260], 1123, 8, 2, 128, 128, seed=91, sigma=4.0, name="peaked")
+    pa, dev, out = run_gpu(case)
+    check_plan(case, pa)
+    f32 = lambda w: wl.bf16_bits_to_f32(case.bits(w, pa.T))
+    q, k, v, do = f32("q"), f32("k"), f32("v"), f32("do")
+    cu = np.asarray(pa.cu, dtype=np.int32)
+    O, LSE = oracle.attn_fwd(q, k, v, cu, None)
+    dQ = oracle.attn_bwd_dq(q, k, v, do, cu, None)
+    dK, dV = oracle.attn_bwd_dkdv(q, k, v, do, cu, None)
+    res = {"o_rel": rel_l2(out["o"], O), "lse_rel": float(np.abs(out["lse"] - LSE).max() / np.abs(LSE).max()),
+           "dq_rel": rel_l2(out["dq"], dQ), "dk_rel": rel_l2(out["dk"], dK), "dv_rel": rel_l2(out["dv"], dV)}
+    print("[parity peaked]", " ".join("%s=%.3e" % kv for kv in res.items()), "max |LSE| %.1f" % np.abs(LSE).max(), flush=True)
+    assert np.isfinite(out["o"]).all() and np.isfinite(out["dq"]).all() and np.isfinite(out["dk"]).all()
+    assert res["o_rel"] <= 1e-2 and res["lse_rel"] <= 1e-3
+    assert max(res["dq_rel"], res["dk_rel"], res["dv_rel"]) <= 1e-2, res
+
+
 def test_forward_is_bit_stable_and_untouched_rows_stay():
     import torch
     case = Case([260, 130], 390, 4, 2, 128, 128, seed=27, name="stable")
