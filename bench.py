@@ -91,6 +91,51 @@ class HipEvents:
         return float(ms.value)
 
 
+class PowerSampler:
+    """Board power from the amdgpu hwmon node, polled from a host thread while the timed steps run (the
+    kernels sit at the board's power limit, which is what bounds them).  Reports nothing
+    when the node cannot be read."""
+
+    def __init__(self, period_s: float = 0.004):
+        import glob
+        import threading
+        self.period = period_s
+        self.samples = []
+        self.stop = False
+        nodes = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input"))
+        self.node = nodes[0] if nodes else None
+        self.cap_w = None
+        if self.node:
+            try:
+                self.cap_w = int(open(self.node.replace("power1_input", "power1_cap")).read()) / 1e6
+            except (OSError, ValueError):
+                pass
+        self.thread = threading.Thread(target=self._run, daemon=True) if self.node else None
+
+    def _run(self):
+        while not self.stop:
+            try:
+                self.samples.append((time.perf_counter(), int(open(self.node).read()) / 1e6))
+            except (OSError, ValueError):
+                return
+            time.sleep(self.period)
+
+    def start(self):
+        if self.thread:
+            self.thread.start()
+
+    def finish(self, t0: float, t1: float):
+        self.stop = True
+        if not self.thread:
+            return None
+        self.thread.join()
+        w = [p for (t, p) in self.samples if t0 <= t <= t1]
+        if not w:
+            return None
+        return {"mean_w": float(np.mean(w)), "max_w": float(np.max(w)), "cap_w": self.cap_w, "samples": len(w),
+                "source": "hwmon power1_input during the timed steps"}
+
+
 def busy_spread(rec: np.ndarray):
     """Per-CU busy time from per-workgroup records -> (max-min)/max, the ABR form, #CUs seen."""
     hw, xcc = rec["hw_id"], rec["xcc_id"] & 0xF
@@ -317,16 +362,20 @@ def main():
         pa.forward(dev["q"], dev["k"], dev["v"])
         pa.backward(dev["q"], dev["k"], dev["v"], dev["do"])
 
+    power = PowerSampler()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    power.start()
     ev.record(e0, stream)
     t_host = time.perf_counter()
     for i in range(K):
         step(i)
     ev.record(e1, stream)
     torch.cuda.synchronize()
-    host_ms = (time.perf_counter() - t_host) * 1e3
+    t_host_end = time.perf_counter()
+    host_ms = (t_host_end - t_host) * 1e3
+    board_power = power.finish(t_host, t_host_end)
     H.hbp_set_kernel_events(H.HBP_FWD, None, None)
     H.hbp_set_kernel_events(H.HBP_BWD, None, None)
     H.hbp_set_kernel_events(H.HBP_BWD_DQ, None, None)
@@ -422,6 +471,7 @@ def main():
                      "traffic_key": {"config": args.config, "seed": args.seed, "kernel_sources_sha256_12": kernel_sources_digest(),
                                      "table": "profiles/hbm_traffic_table.md"}},
         "busy_time_spread": {"fwd": spread_f, "bwd_dkdv": spread_b, "bwd_dq": spread_q},
+        "board_power": board_power,
     }
     if graph_info:
         out["graph_replay"] = graph_info
