@@ -93,7 +93,7 @@ class HipEvents:
 
 class PowerSampler:
     """Board power from the amdgpu hwmon node, polled from a host thread while the timed steps run (the
-    kernels sit at the board's power limit, which is what bounds them; see DESIGN.md).  Reports nothing
+    kernels sit at the board's power limit, which is what bounds them).  Reports nothing
     when the node cannot be read."""
 
     def __init__(self, period_s: float = 0.004):
