@@ -9,6 +9,17 @@ import oracle
 
 # bars (max-abs / mean-abs on O, max-abs on LSE, relative L2 on gradients)
 O_MAX, O_MEAN, LSE_MAX, GRAD_REL = 2e-2, 2e-3, 1e-3, 1e-2
+# A relative bar has no meaning where the reference is exactly zero: in a pack of one-token samples dQ and dK
+# vanish identically (P = 1, dP = D), while the kernel forms D from its own fp32 sums and leaves values of
+# the order 1e-7.  Such a tensor passes when its root-mean-square error stays below GRAD_ABS_RMS, five orders
+# of magnitude under the resolution of a bf16 value of unit size; everywhere else the relative bar decides.
+GRAD_ABS_RMS = 1e-5
+
+
+def grad_ok(a, ref):
+    """||a - ref|| <= GRAD_REL ||ref||, or (vanishing reference) rms(a - ref) <= GRAD_ABS_RMS."""
+    err = float(np.linalg.norm((a - ref).ravel()))
+    return err <= GRAD_REL * float(np.linalg.norm(ref.ravel())) or err <= GRAD_ABS_RMS * np.sqrt(max(a.size, 1))
 
 
 def rel_l2(a, ref):
@@ -88,18 +99,18 @@ def compare(case: Case, pa, out, q_heads=None, rows=None, cols=None, label=""):
     g_dq = out["dq"][rsel][:, q_heads]
     res = {"o_max": float(np.abs(g_o - O).max()), "o_mean": float(np.abs(g_o - O).mean()),
            "lse_max": float(np.abs(g_lse - LSE).max()), "dq_rel": rel_l2(g_dq, dQ)}
+    grads_ok = grad_ok(g_dq, dQ)
     if whole:
         csel = slice(None) if cols is None else np.asarray(cols)
         dK, dV = oracle.attn_bwd_dkdv(q, k, v, do, cu, scale, cols=cols)
         res["dk_rel"] = rel_l2(out["dk"][csel][:, kv_heads], dK)
         res["dv_rel"] = rel_l2(out["dv"][csel][:, kv_heads], dV)
+        grads_ok = grads_ok and grad_ok(out["dk"][csel][:, kv_heads], dK) and grad_ok(out["dv"][csel][:, kv_heads], dV)
     print("[parity %s %s] %s" % (case.name, label, " ".join("%s=%.3e" % kv for kv in res.items())), flush=True)
     assert np.isfinite(list(res.values())).all(), res
     assert res["o_max"] <= O_MAX and res["o_mean"] <= O_MEAN, res
     assert res["lse_max"] <= LSE_MAX, res
-    assert res["dq_rel"] <= GRAD_REL, res
-    if whole:
-        assert res["dk_rel"] <= GRAD_REL and res["dv_rel"] <= GRAD_REL, res
+    assert grads_ok, res
     return res
 
 

@@ -38,6 +38,14 @@ def test_many_one_token_samples_and_single_sample():
     full(Case([777], 777, 2, 1, 128, 128, seed=25, name="single-sample"))
 
 
+def test_packs_of_one_token_samples_only():
+    """dQ and dK are identically zero here (every probability is 1, dP = D); the kernels' values must vanish
+    to rounding (see GRAD_ABS_RMS), dV = the sum of dO over the group, O = V, LSE = the one score."""
+    for lengths, Hq, Hkv, d, e in (([1], 8, 1, 192, 128), ([1, 1, 1, 1, 1], 4, 2, 128, 128), ([1] * 70, 2, 2, 64, 64)):
+        pa, dev, out = full(Case(lengths, len(lengths), Hq, Hkv, d, e, seed=29, name="ones-%d" % len(lengths)))
+        assert np.abs(out["dq"]).max() <= 1e-4 and np.abs(out["dk"]).max() <= 1e-4
+
+
 def test_explicit_scale_and_small_sigma():
     full(Case([190, 66], 256, 4, 4, 64, 64, seed=26, sigma=0.5, scale=0.2, name="scale"))
 
