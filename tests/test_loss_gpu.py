@@ -9,8 +9,12 @@ pytestmark = pytest.mark.gpu
 # token losses are fp32 sums of up to 131072 terms over exactly representable bf16 inputs
 TOKEN_LOSS_ABS = 2e-5
 LOSS_REL = 2e-6
-# gradients are stored in bf16 (relative rounding 2^-9 per element)
-GRAD_REL_L2 = 3e-3
+# Gradients are stored in bf16: 8 significant bits, so a stored value is off by up to 2^-8 = 3.9e-3 of itself.
+# Entries round independently and the relative L2 error of a row usually comes out near 2^-8 / sqrt(3) / 1.5, but
+# when the large entries of a gradient are all the same number (rows dominated by their one-hot term -w, with a
+# weight w such as 1/13 that bf16 does not hold) the whole tensor carries that one rounding error; the bar is the
+# bound itself plus the fp32 arithmetic in front of the rounding.
+GRAD_REL_L2 = 4e-3
 
 
 def make_case(lens, V, seed, sigma=2.0, p_mask=0.3, stride=None):
