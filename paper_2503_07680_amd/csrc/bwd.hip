@@ -4,7 +4,7 @@
 // (2) dq        query-tile major, same skeleton as the forward: work item = (query tile of <=128
 //               rows, query head); K and V tiles of 64 keys stream through LDS; per 32-key block
 //                   S^T  = K Q^T,  dP^T = V dO^T          (one query per lane column)
-//                   dS^T = exp2(S^T c - LSE log2e) (dP^T - D)
+//                   dS^T = exp2(S^T c - LSE log2e) (dP^T - D)      (the dP^T accumulator starts at -D)
 //                   dQ^T += K^T dS^T                      (K^T by transposing LDS reads)
 // (3) dkdv      key-tile major: work item = (key tile of <=128 keys, kv head); each wavefront keeps
 //               the K and V fragments of its 32 keys and the dK^T / dV^T accumulators in registers
@@ -64,7 +64,7 @@ __global__ __launch_bounds__(kThreads, DQK <= 128 ? 2 : 1) void bwd_dq_kernel(co
   constexpr int KRB = DQK * 2, VRB = DV * 2;
   constexpr int K_TILE = BN * KRB, V_TILE = BN * VRB;
   constexpr int NC = DQK / 16, NCV = DV / 16, NDB = DQK / 32;
-  constexpr int PD = 4;
+  constexpr int PD = DQK == 128 ? 3 : 4;  // read-ahead depth: at d = 128 the kernel is two registers short of its 256 with 4
   // Scores in the vector file (asm MFMA): needs a kernel that compiles without spills (checked at build
   // time); the builtin form stays as the fallback.
   constexpr bool kVgprScores = true;
@@ -81,11 +81,16 @@ __global__ __launch_bounds__(kThreads, DQK <= 128 ? 2 : 1) void bwd_dq_kernel(co
   // Absolute LDS addresses of this lane's fragments: workgroup base and current buffer included
   // (toggled once per tile), so a read needs no address arithmetic.
   const uint32_t lds0 = lds_address(smem);
-  uint32_t koff[NC], vnoff[NCV], ktoff[2][NDB];
+  // With equal row sizes (d_qk = d_v) a lane's V fragments sit exactly two K tiles behind its K fragments
+  // (both buffers toggle together), so one set of addresses serves both.
+  constexpr bool kSameRows = DQK == DV;
+  uint32_t koff[NC], vnoff[kSameRows ? 1 : NCV], ktoff[2][NDB];
 #pragma unroll
   for (int c = 0; c < NC; ++c) koff[c] = lds0 + l32 * KRB + swz<DQK>(2 * c + hh, l32) * 16;
+  if (!kSameRows) {
 #pragma unroll
-  for (int c = 0; c < NCV; ++c) vnoff[c] = lds0 + 2 * K_TILE + l32 * VRB + swz<DV>(2 * c + hh, l32) * 16;
+    for (int c = 0; c < NCV; ++c) vnoff[c] = lds0 + 2 * K_TILE + l32 * VRB + swz<DV>(2 * c + hh, l32) * 16;
+  }
   {
     const int G = lane >> 4, s = lane & 15;
     const int k8 = 4 * hh + (s >> 2);
@@ -99,9 +104,9 @@ __global__ __launch_bounds__(kThreads, DQK <= 128 ? 2 : 1) void bwd_dq_kernel(co
   }
 
   TileLoader<DQK, BN> k_loader;
-  TileLoader<DV, BN> v_loader;
+  TileLoader<DV, BN> v_loader;  // same lane pattern as k_loader when the row sizes agree: then only that one is kept
   k_loader.init(wave, lane);
-  v_loader.init(wave, lane);
+  if (!kSameRows) v_loader.init(wave, lane);
   const uint32_t k_stride_b = (uint32_t)p.k_st * 2, v_stride_b = (uint32_t)p.v_st * 2;
 
   ProfAcc pa;
@@ -137,7 +142,10 @@ __global__ __launch_bounds__(kThreads, DQK <= 128 ? 2 : 1) void bwd_dq_kernel(co
         const int k_off = kt * BN;
         const int valid = n_keys - k_off;
         k_loader.issue(kbase + (int64_t)k_off * p.k_st, k_stride_b, valid, k_lds + (kt & 1) * K_TILE, wave);
-        v_loader.issue(vbase + (int64_t)k_off * p.v_st, v_stride_b, valid, v_lds + (kt & 1) * V_TILE, wave);
+        if constexpr (kSameRows)
+          k_loader.issue(vbase + (int64_t)k_off * p.v_st, v_stride_b, valid, v_lds + (kt & 1) * V_TILE, wave);
+        else
+          v_loader.issue(vbase + (int64_t)k_off * p.v_st, v_stride_b, valid, v_lds + (kt & 1) * V_TILE, wave);
       };
       issue(0);
 
@@ -155,6 +163,12 @@ __global__ __launch_bounds__(kThreads, DQK <= 128 ? 2 : 1) void bwd_dq_kernel(co
           Dv = p.D[(int64_t)h * p.T + my_row];
         }
       }
+      // the dP^T accumulator of every block starts at -D of the lane's query (one value per lane): the
+      // subtraction in dS = P (dP - D) then comes out of the MFMAs
+      f32x16 negD;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) negD[i] = -Dv;
+      asm volatile("" : "+v"(negD));
       f32x16 dqacc[NDB];
 #pragma unroll
       for (int db = 0; db < NDB; ++db)
@@ -162,7 +176,7 @@ __global__ __launch_bounds__(kThreads, DQK <= 128 ? 2 : 1) void bwd_dq_kernel(co
         for (int i = 0; i < 16; ++i) dqacc[db][i] = 0.f;
       const int q_in = qw0 + l32;
 
-      // One 32-key block: sd = (S^T, dP^T) products, sm = dS^T = exp2(c S^T - LSE2)(dP^T - D),
+      // One 32-key block: sd = (S^T, dP^T - D) products, sm = dS^T = exp2(c S^T - LSE2)(dP^T - D),
       // gr = dQ^T += K^T dS^T.  Interior tiles pipeline their two blocks inside the wave:
       //     sd(0) | sd(1) + sm(0) | gr(0) + sm(1) first half | gr(1) first half + sm(1) rest | gr(1) rest
       struct Blk {
@@ -173,6 +187,7 @@ __global__ __launch_bounds__(kThreads, DQK <= 128 ? 2 : 1) void bwd_dq_kernel(co
         return [&, blk](int i) {
           Frag a;
           if (i < NC) a.u = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(koff[i] + 32 * blk * KRB);
+          else if (kSameRows) a.u = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(koff[i - NC] + 2 * K_TILE + 32 * blk * VRB);
           else a.u = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(vnoff[i - NC] + 32 * blk * VRB);
           return a;
         };
@@ -182,7 +197,7 @@ __global__ __launch_bounds__(kThreads, DQK <= 128 ? 2 : 1) void bwd_dq_kernel(co
           if (kVgprScores) {
             if (i == 0) x.s = mfma32_vgpr_first(a.v, qf[0].v);
             else if (i < NC) mfma32_vgpr(x.s, a.v, qf[i].v);
-            else if (i == NC) x.dp = mfma32_vgpr_first(a.v, dof[0].v);
+            else if (i == NC) x.dp = mfma32_vgpr_from(a.v, dof[0].v, negD);  // starts at -D: ends as dP - D
             else mfma32_vgpr(x.dp, a.v, dof[i - NC].v);
           } else {
             if (i == 0 || i == NC) {
@@ -190,7 +205,7 @@ __global__ __launch_bounds__(kThreads, DQK <= 128 ? 2 : 1) void bwd_dq_kernel(co
 #pragma unroll
               for (int e = 0; e < 16; ++e) z[e] = 0.f;
               if (i == 0) x.s = mfma32(a.v, qf[0].v, z);
-              else x.dp = mfma32(a.v, dof[0].v, z);
+              else x.dp = mfma32(a.v, dof[0].v, negD);
             } else if (i < NC) {
               x.s = mfma32(a.v, qf[i].v, x.s);
             } else {
@@ -218,7 +233,7 @@ __global__ __launch_bounds__(kThreads, DQK <= 128 ? 2 : 1) void bwd_dq_kernel(co
           if (decltype(masked)::value) {
             if (kb + 8 * (e >> 2) + 4 * hh + (e & 3) > q_in) pr = 0.f;
           }
-          const float ds = pr * (x.dp[e] - Dv);
+          const float ds = pr * x.dp[e];
           if (e & 1) x.dsf[e >> 3].w[(e & 7) >> 1] = pack_bf16(ds_even, ds);
           else ds_even = ds;
         }
@@ -229,8 +244,10 @@ __global__ __launch_bounds__(kThreads, DQK <= 128 ? 2 : 1) void bwd_dq_kernel(co
         const int dk = buf ? K_TILE : -K_TILE, dv = buf ? V_TILE : -V_TILE;
 #pragma unroll
         for (int c = 0; c < NC; ++c) koff[c] += dk;
+        if (!kSameRows) {
 #pragma unroll
-        for (int c = 0; c < NCV; ++c) vnoff[c] += dv;
+          for (int c = 0; c < NCV; ++c) vnoff[c] += dv;
+        }
 #pragma unroll
         for (int r = 0; r < 2; ++r)
 #pragma unroll

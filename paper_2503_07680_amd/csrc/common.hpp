@@ -35,6 +35,12 @@ __device__ __forceinline__ f32x16 mfma32_vgpr_first(bf16x8 a, bf16x8 b) {
   asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "v"(b));
   return d;
 }
+// first MFMA of a chain whose accumulator starts from another register tuple (left untouched)
+__device__ __forceinline__ f32x16 mfma32_vgpr_from(bf16x8 a, bf16x8 b, const f32x16& c0) {
+  f32x16 d;
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(d) : "v"(a), "v"(b), "v"(c0));
+  return d;
+}
 __device__ __forceinline__ void mfma32_vgpr(f32x16& c, bf16x8 a, bf16x8 b) {
   asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b));
 }
