@@ -42,7 +42,7 @@ struct FwdWave {
   static constexpr int PD = 4;          // LDS read-ahead depth of the operand ring
   static constexpr int NSL = 17;        // exp slices: 1..16 = elements, 17 = drain
   static constexpr int EA = NSL * 2 * NC / (2 * NC + NB);  // exp slices placed behind the A MFMAs
-  static constexpr int NMP = 5;         // pieces of the row-maximum computation
+  static constexpr int NMP = 4;         // pieces of the diagonal block's mask
 
   // LDS layout: [K buf0][K buf1][V buf0][V buf1].  The offsets below are absolute LDS addresses
   // (workgroup base and current buffer included), so a read needs no address arithmetic.
@@ -55,11 +55,10 @@ struct FwdWave {
   Frag pf[2][2];         // pf[b & 1][j] = probabilities of block b, key chunk j
   float scale_log2;
   int q_in, hh;
-  // Online softmax state.  m_run: reference the probabilities of the current block are taken
-  // against; l_run: this lane's part of the row sum.  m_next / alpha_next / move_next: decided by
-  // the row maximum of the following block, adopted when that block becomes the current one.
-  float m_run, l_run, m_next, alpha_next, alpha_cur, pmax;
-  bool move_next, move_cur;
+  // Online softmax state.  m_run: reference the probabilities are taken against (times log2 e): the
+  // maximum of the row's first block, moved up when a later block rises well above it (see
+  // range_check); l_run: this lane's part of the row sum.
+  float m_run, l_run, pmax;
   float p_cur, p_even, psum;
 
   __device__ __forceinline__ Frag k_frag(int blk_in_tile, int c) const {
@@ -98,35 +97,64 @@ struct FwdWave {
     c.run(load, [&](int i, const Frag& f) { s[0] = mfma32(f.v, qf[i].v, s[0]); });
   }
 
-  // Row maximum of a block (scores in s[par]) in NMP pieces, and with it the decision whether the
-  // reference moves when this block becomes the current one.  d: causal threshold of this lane,
-  // element i of the block is masked iff 8 (i>>2) + (i&3) > d (pass mask = false for blocks that
-  // lie entirely below the diagonal).
-  // Lazy rescale: a row's reference only moves when its maximum grew by more than 2^8; until
-  // then probabilities are taken relative to the old reference (they stay below 2^8, and O and l
-  // share the reference, so the result is unchanged).
-  template <bool MAYBE_MASKED>
-  __device__ __forceinline__ void max_piece(int par, int d, int piece) {
-    if (piece < 4) {
-      if (piece == 0) pmax = -INFINITY;
+  // The reference of a row.  Probabilities are exp2(s c - m_run) against a reference that O and l share,
+  // so the result does not depend on it; it starts as the maximum of the row's first block of 32 keys.
+  // No later block computes its row maximum up front.  Instead the block's probabilities are taken against
+  // the reference as it stands, and their sum tells whether that was good enough: a lane's sum of 16
+  // probabilities above 2^8 means that some score lies well above the reference, and only then
+  // (range_check, a wave-uniform branch that ordinary data takes for a few early blocks of an item) the
+  // true maximum of the block is computed, the reference moves there, O and l are rescaled and the block's
+  // probabilities are taken again.  A row's largest score so far thus never lies more than 8 (in log2)
+  // above its reference, as with a maximum computed for every block, and a dominant key still gets the
+  // probability 1 exactly; but the hot loop carries no row maximum at all: per element one fma, one exp2,
+  // one add and half a conversion.
+  //
+  // Block 0 (scores in s[0]): mask (d: causal threshold of this lane, element i is masked iff
+  // 8 (i>>2) + (i&3) > d), maximum, reference.
+  __device__ __forceinline__ void first_reference(int d) {
+    pmax = -INFINITY;
 #pragma unroll
-      for (int i = 4 * piece; i < 4 * piece + 4; ++i) {
-        if (MAYBE_MASKED) {
-          if (8 * (i >> 2) + (i & 3) > d) s[par][i] = -INFINITY;
-        }
-        pmax = fmaxf(pmax, s[par][i]);
-      }
-      pin(pmax);
-      return;
+    for (int i = 0; i < 16; ++i) {
+      if (8 * (i >> 2) + (i & 3) > d) s[0][i] = -INFINITY;
+      pmax = fmaxf(pmax, s[0][i]);
     }
-    const float mx = max_with_other_half(pmax) * scale_log2;  // scale > 0: max commutes with the scaling
-    // decided row by row (both lanes of a row see the same mx), so the choice is a plain vector
-    // select; the wave-wide "did any row move" is only needed a phase later, for O
-    const bool grew = mx > m_run + 8.0f;
-    m_next = grew ? fmaxf(m_run, mx) : m_run;  // finite: key 0 of the sample is visible to every row
-    alpha_next = __builtin_amdgcn_exp2f(m_run - m_next);
-    move_next = __builtin_amdgcn_ballot_w64(grew) != 0;
-    pin(alpha_next);
+    m_run = max_with_other_half(pmax) * scale_log2;  // scale > 0; finite: key 0 of the sample is visible to every row
+    l_run = 0.f;
+  }
+  // causal mask of a later block (scores in s[par]), four elements per piece
+  __device__ __forceinline__ void mask_piece(int par, int d, int piece) {
+#pragma unroll
+    for (int i = 4 * piece; i < 4 * piece + 4; ++i)
+      if (8 * (i >> 2) + (i & 3) > d) s[par][i] = -INFINITY;
+  }
+  // After the exp slices of a block (scores still in s[par], probabilities in pf[par], this lane's sum in
+  // psum): if any lane's sum says that the block rose above the reference (or is not a number at all),
+  // move the references to the rows' true maxima, rescale O and l, and take the block's probabilities
+  // again.  Then the sum joins l.
+  __device__ __forceinline__ void range_check(int par) {
+    if (__builtin_amdgcn_ballot_w64(!(psum < 0x1p8f)) != 0) {
+      float mx = -INFINITY;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[par][i]);
+      const float m_new = fmaxf(m_run, max_with_other_half(mx) * scale_log2);
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+      m_run = m_new;
+      l_run *= alpha;
+#pragma unroll
+      for (int eb = 0; eb < NEB; ++eb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) oacc[eb][i] *= alpha;
+      psum = 0.f;
+#pragma unroll
+      for (int e = 0; e < 16; e += 2) {
+        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[par][e], scale_log2, -m_run));
+        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[par][e + 1], scale_log2, -m_run));
+        psum += p0;
+        psum += p1;
+        pf[par][e >> 3].w[(e & 7) >> 1] = pack_bf16(p0, p1);
+      }
+    }
+    l_run += psum;
   }
   // causal threshold for the block that starts at in-sample key k_blk; a lane-constant.  Kept
   // opaque so the compares stay "constant vs one register" instead of sixteen precomputed
@@ -136,14 +164,8 @@ struct FwdWave {
     asm volatile("" : "+v"(d));
     return d;
   }
-  // the block whose maximum was just taken becomes the current one
-  __device__ __forceinline__ void adopt() {
-    m_run = m_next;
-    l_run *= alpha_next;
-    alpha_cur = alpha_next;
-    move_cur = move_next;
-    psum = 0.f;
-  }
+  // a new block becomes the current one
+  __device__ __forceinline__ void adopt() { psum = 0.f; }
   // exp of the current block (scores in s[par]).  Elements go through two stages one slice apart
   // (exp of element e next to the sum/pack of element e-1) so no instruction waits on the one
   // before it.  sl = 1..NSL.
@@ -164,13 +186,12 @@ struct FwdWave {
         p_even = p_prev;
       }
     }
-    if (sl == NSL) l_run += psum;
   }
 
   // What phase b of a wave consists of.  The wave's blocks are 0..nb-1; block nb-1 is the diagonal
   // one, the only one that needs the causal compare.
   struct Parts {
-    bool a;     // A(b+1) and the row maximum of block b+1:  b+1 < nb
+    bool a;     // A(b+1) and, on the diagonal, the mask of block b+1:  b+1 < nb
     bool e;     // exp of block b:                             b < nb
     bool b;     // B(b-1):                                     1 <= b <= nb
     bool mask;  // block b+1 is the diagonal block
@@ -180,8 +201,9 @@ struct FwdWave {
   }
 
   // Phase b (PAR = b & 1).  MFMAs: A(b+1) then B(b-1), both on block 1-PAR of their tiles.  Behind
-  // them: the exp slices of block b, and behind the B MFMAs (when the scores of block b+1 are
-  // complete) the pieces of that block's row maximum.  HOT: every part present and no mask, known
+  // them: the exp slices of block b and, where block b+1 is the diagonal one, behind the B MFMAs (when
+  // its scores are complete) the pieces of its mask; at the end the check whether block b rose above
+  // the rows' references (range_check).  HOT: every part present and no mask, known
   // at compile time; otherwise `pt` says (wave-uniform) which parts run.  With part a the ring must
   // hold the first PD K fragments on entry; an odd phase leaves the ring holding those of the
   // following even phase (same K tile, no barrier in between).  k_next: in-sample index of the
@@ -193,7 +215,6 @@ struct FwdWave {
     int d = 0;
     if (!HOT) d = mask_threshold(k_next, pt.mask);
     if (do_e) adopt();
-    else move_cur = false;
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int j = 0; j < TOTAL; ++j) {
@@ -224,22 +245,17 @@ struct FwdWave {
 #pragma unroll
         for (int sl = lo; sl < hi; ++sl) exp_slice(PAR, sl + 1);
       }
-      if (do_a && j >= NC) {
+      if (!HOT && do_a && pt.mask && j >= NC) {  // the scores of block b+1 are complete: mask the diagonal block
 #pragma unroll
         for (int piece = 0; piece < NMP; ++piece) {
           const int slot = 2 + piece * (NB - 2) / NMP;
-          if ((slot < NB ? slot : NB - 1) == j - NC) max_piece<!HOT>(NXT, d, piece);
+          if ((slot < NB ? slot : NB - 1) == j - NC) mask_piece(NXT, d, piece);
         }
       }
       copy(j);
       __builtin_amdgcn_sched_barrier(0);
     }
-    if (move_cur) {  // blocks up to b-1 are in O: bring them to the reference block b was taken against
-#pragma unroll
-      for (int eb = 0; eb < NEB; ++eb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) oacc[eb][i] *= alpha_cur;
-    }
+    if (do_e) range_check(PAR);
   }
   template <int PAR>
   __device__ __forceinline__ void any_phase(int b, int nb) {
@@ -361,7 +377,7 @@ __global__ __launch_bounds__(kThreads * HP * TP, 2 / (HP * TP)) void fwd_kernel(
       for (int eb = 0; eb < NEB; ++eb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) w.oacc[eb][i] = 0.f;
-      w.m_run = -INFINITY;
+      w.m_run = 0.f;
       w.l_run = 0.f;
       w.q_in = qw0 + l32;
       w.p_cur = w.p_even = w.psum = 0.f;
@@ -402,10 +418,7 @@ __global__ __launch_bounds__(kThreads * HP * TP, 2 / (HP * TP)) void fwd_kernel(
       if (nb > 0) {
         w.first_scores();
         w.preload_k(1);
-        const int d0 = w.mask_threshold(0, nb == 1);
-#pragma unroll
-        for (int piece = 0; piece < W::NMP; ++piece) w.template max_piece<true>(0, d0, piece);
-        w.move_next = false;  // O is still zero: nothing to rescale
+        w.first_reference(w.mask_threshold(0, nb == 1));
       }
 
       // Tiles whose two phases both run every part unmasked (phases 1 .. nb-3) get a loop of

@@ -74,6 +74,45 @@ def test_peaked_softmax_with_large_logits():
     assert max(res["dq_rel"], res["dk_rel"], res["dv_rel"]) <= 1e-2, res
 
 
+def test_scores_that_grow_along_the_sample_move_the_reference():
+    """The forward takes every probability of a row against one reference, the maximum of the row's first 32
+    keys, and moves it only when a later block would leave the range of fp32.  Here the keys grow along the
+    sample (|K| rises from 1 to 40 times its start), so later scores exceed the first block's by hundreds of
+    units and the reference must move, several times per row; a second sample has its large keys FIRST (the
+    reference never moves and most later probabilities underflow).  Relative bars as in the peaked case."""
+    import oracle
+    import torch
+    from paper_2503_07680_amd.runner import PackedAttention
+    from parity_util import rel_l2
+    lengths, Hq, Hkv, d, e = [900, 700, 70], 4, 2, 128, 128
+    T = sum(lengths)
+    rng = np.random.default_rng(93)
+    ramp = np.concatenate([np.linspace(1.0, 40.0, 900), np.linspace(40.0, 1.0, 700), np.linspace(1.0, 25.0, 70)])
+    bf = lambda x: wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(x.astype(np.float32)))
+    q = bf(rng.standard_normal((T, Hq, d)))
+    k = bf(rng.standard_normal((T, Hkv, d)) * ramp[:, None, None])
+    v = bf(rng.standard_normal((T, Hkv, e)))
+    do = bf(rng.standard_normal((T, Hq, e)))
+    pa = PackedAttention(lengths, T, Hq, Hkv, d, e)
+    dev = [pa.to_device_bf16(wl.f32_to_bf16_bits(x)) for x in (q, k, v, do)]
+    pa.forward(*dev[:3])
+    pa.backward(*dev)
+    torch.cuda.synchronize()
+    cu = np.asarray(pa.cu, dtype=np.int32)
+    O, LSE = oracle.attn_fwd(q, k, v, cu, None)
+    dQ = oracle.attn_bwd_dq(q, k, v, do, cu, None)
+    dK, dV = oracle.attn_bwd_dkdv(q, k, v, do, cu, None)
+    got = {n: t.float().cpu().numpy() for n, t in (("o", pa.o), ("dq", pa.dq), ("dk", pa.dk), ("dv", pa.dv))}
+    lse = pa.lse.cpu().numpy()
+    res = {"o_rel": rel_l2(got["o"], O), "lse_rel": float(np.abs(lse - LSE).max() / np.abs(LSE).max()),
+           "dq_rel": rel_l2(got["dq"], dQ), "dk_rel": rel_l2(got["dk"], dK), "dv_rel": rel_l2(got["dv"], dV)}
+    print("[parity growing-scores]", " ".join("%s=%.3e" % kv for kv in res.items()),
+          "LSE from %.1f to %.1f" % (LSE.min(), LSE.max()), flush=True)
+    assert all(np.isfinite(x).all() for x in got.values()) and np.isfinite(lse).all()
+    assert res["o_rel"] <= 1e-2 and res["lse_rel"] <= 1e-3
+    assert max(res["dq_rel"], res["dk_rel"], res["dv_rel"]) <= 1e-2, res
+
+
 def test_forward_is_bit_stable_and_untouched_rows_stay():
     import torch
     case = Case([260, 130], 390, 4, 2, 128, 128, seed=27, name="stable")
