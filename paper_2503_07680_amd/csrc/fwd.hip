@@ -61,23 +61,25 @@ struct FwdWave {
   float m_run, l_run, pmax;
   float p_cur, p_even, psum;
 
-  __device__ __forceinline__ Frag k_frag(int blk_in_tile, int c) const {
+  // `add`: a compile-time byte offset on top of the lane's offsets (the hot loop names the other tile
+  // buffer this way, as part of the read's immediate, instead of moving the offsets every tile)
+  __device__ __forceinline__ Frag k_frag(int blk_in_tile, int c, int add = 0) const {
     Frag f;
-    f.u = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(koff[c] + 32 * blk_in_tile * KRB);
+    f.u = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(koff[c] + (32 * blk_in_tile * KRB + add));
     return f;
   }
-  __device__ __forceinline__ Frag v_frag(int blk_in_tile, int i) const {  // i = (j, eb), eb fastest
+  __device__ __forceinline__ Frag v_frag(int blk_in_tile, int i, int add = 0) const {  // i = (j, eb), eb fastest
     const int eb = i % NEB, j = i / NEB;
-    const uint32_t base = (32 * blk_in_tile + 16 * j) * VRB;
+    const uint32_t base = (32 * blk_in_tile + 16 * j) * VRB + add;
     Frag f;
     f.h[0] = lds_read_tr16_at(voff[0][eb] + base);
     f.h[1] = lds_read_tr16_at(voff[1][eb] + base);
     return f;
   }
   // first PD operands of a phase that reads K block `blk_in_tile`
-  __device__ __forceinline__ void preload_k(int blk_in_tile) {
+  __device__ __forceinline__ void preload_k(int blk_in_tile, int add = 0) {
 #pragma unroll
-    for (int i = 0; i < PD; ++i) ring[i] = k_frag(blk_in_tile, i);
+    for (int i = 0; i < PD; ++i) ring[i] = k_frag(blk_in_tile, i, add);
   }
 
   // Values produced by the slices are consumed a phase later, behind a branch; without an anchor
@@ -207,8 +209,9 @@ struct FwdWave {
   // at compile time; otherwise `pt` says (wave-uniform) which parts run.  With part a the ring must
   // hold the first PD K fragments on entry; an odd phase leaves the ring holding those of the
   // following even phase (same K tile, no barrier in between).  k_next: in-sample index of the
-  // first key of block b+1.
-  template <int PAR, bool HOT, class Copy>
+  // first key of block b+1.  KADD, VADD: byte offsets of the K and V tile buffers this phase reads,
+  // relative to where the lane's offsets point.
+  template <int PAR, bool HOT, int KADD = 0, int VADD = 0, class Copy>
   __device__ __forceinline__ void phase(int k_next, Parts pt, Copy copy) {
     constexpr int NXT = 1 - PAR;
     const bool do_a = HOT || pt.a, do_e = HOT || pt.e, do_b = HOT || pt.b;
@@ -233,11 +236,11 @@ struct FwdWave {
       }
       const int jn = j + PD;  // operand to fetch now
       if (jn < NC) {
-        if (do_a) ring[jn % PD] = k_frag(NXT, jn);
+        if (do_a) ring[jn % PD] = k_frag(NXT, jn, KADD);
       } else if (jn < TOTAL) {
-        if (do_b) ring[jn % PD] = v_frag(NXT, jn - NC);
+        if (do_b) ring[jn % PD] = v_frag(NXT, jn - NC, VADD);
       } else if (PAR == 1) {
-        ring[jn % PD] = k_frag(PAR, jn - TOTAL);
+        ring[jn % PD] = k_frag(PAR, jn - TOTAL, KADD);
       }
       if (do_e) {
         const int lo = j < NC ? j * EA / NC : EA + (j - NC) * (NSL - EA) / NB;
@@ -434,34 +437,63 @@ __global__ __launch_bounds__(kThreads * HP * TP, 2 / (HP * TP)) void fwd_kernel(
         race_fence();
         t = 1;
       }
-      for (; t < t_hot_end; ++t) {
-        w.template phase<0, true>(64 * t + 32, typename W::Parts{}, [](int) {});
+      // One hot tile t: phase 2t reads K tile t and V tile t-1, phase 2t+1 reads K tile t+1 and V tile t.
+      // TPAR = t & 1 as a compile-time constant: the lane's offsets stay on buffer 0 and the other buffer
+      // is part of each read's immediate offset; TPAR < 0: the offsets follow the buffers (16 vector adds
+      // per tile, but one copy of the code).
+      auto hot_tile = [&](auto tpar, int t) {
+        constexpr int TPAR = decltype(tpar)::value;
+        constexpr bool IMM = TPAR >= 0;
+        w.template phase<0, true, IMM ? TPAR * K_TILE : 0, IMM ? (1 - TPAR) * V_TILE : 0>(
+            64 * t + 32, typename W::Parts{}, [](int) {});
         race_fence();
-        tile_sync(t);
-        w.preload_k(0);
+        if constexpr (IMM) {
+          wait_async_loads();
+          __syncthreads();  // K(t+1) and V(t) have landed; K(t) and V(t-1) are no longer read
+        } else {
+          tile_sync(t);
+        }
+        w.preload_k(0, IMM ? (1 - TPAR) * K_TILE : 0);
         // the copies of K(t+2) and V(t+1) go out one at a time behind this phase's MFMAs (a burst
         // of them would hold the wave for as long as the address path takes to drain)
         const uint16_t* kg = kbase + (int64_t)(t + 2) * BN * p.k_st;
         const uint16_t* vg = vbase + (int64_t)(t + 1) * BN * p.v_st;
         const int k_valid = n_keys - (t + 2) * BN, v_valid = n_keys - (t + 1) * BN;
-        const char* k_dst = k_lds + (t & 1) * K_TILE;
-        const char* v_dst = v_lds + ((t + 1) & 1) * V_TILE;
+        const char* k_dst = k_lds + (IMM ? TPAR : t & 1) * K_TILE;
+        const char* v_dst = v_lds + (IMM ? 1 - TPAR : (t + 1) & 1) * V_TILE;
         constexpr int NKC = decltype(k_loader)::PER_WAVE, NVC = decltype(v_loader)::PER_WAVE;
         constexpr int GAP = W::TOTAL / (NKC + NVC) > 0 ? W::TOTAL / (NKC + NVC) : 1;
-        w.template phase<1, true>(64 * t + 64, typename W::Parts{}, [&](int j) {
+        w.template phase<1, true, IMM ? (1 - TPAR) * K_TILE : 0, IMM ? TPAR * V_TILE : 0>(
+            64 * t + 64, typename W::Parts{}, [&](int j) {
 #pragma unroll
-          for (int c = 0; c < NKC + NVC; ++c) {
-            const int slot = c * GAP < W::TOTAL ? c * GAP : W::TOTAL - 1;
-            if (slot != j) continue;
-            if (c < NKC) {
-              if (k_valid > 0) k_loader.issue_one(c, kg, k_stride_b, k_valid, k_dst, wave, lane);
-            } else {
-              v_loader.issue_one(c - NKC, vg, v_stride_b, v_valid, v_dst, wave, lane);
-            }
-          }
-        });
+              for (int c = 0; c < NKC + NVC; ++c) {
+                const int slot = c * GAP < W::TOTAL ? c * GAP : W::TOTAL - 1;
+                if (slot != j) continue;
+                if (c < NKC) {
+                  if (k_valid > 0) k_loader.issue_one(c, kg, k_stride_b, k_valid, k_dst, wave, lane);
+                } else {
+                  v_loader.issue_one(c - NKC, vg, v_stride_b, v_valid, v_dst, wave, lane);
+                }
+              }
+            });
         race_fence();
+      };
+      // Two copies of the hot tile need a few registers more; at head size 192 they are not there.
+      if constexpr (DQK <= 128) {
+        if (t + 1 < t_hot_end) {
+          point_k(0);
+          point_v(0);
+        }
+        for (; t + 1 < t_hot_end; t += 2) {  // t is odd here: the hot tiles start at tile 1
+          hot_tile(std::integral_constant<int, 1>{}, t);
+          hot_tile(std::integral_constant<int, 0>{}, t + 1);
+        }
+        if (t > 0) {  // back to offsets that follow the buffers: K tile t, V tile t-1 are read next
+          point_k(t & 1);
+          point_v((t - 1) & 1);
+        }
       }
+      for (; t < t_hot_end; ++t) hot_tile(std::integral_constant<int, -1>{}, t);
       for (; t < nkt; ++t) {
         w.template any_phase<0>(2 * t, nb);
         race_fence();
