@@ -183,12 +183,15 @@ __global__ __launch_bounds__(kThreads, DQK <= 128 ? 2 : 1) void bwd_dq_kernel(co
         f32x16 s, dp;
         Frag dsf[2];
       };
-      auto sd_load = [&](int blk) {
-        return [&, blk](int i) {
+      // buf: a compile-time tile buffer on top of where the lane's offsets point (the interior loop names
+      // the second buffer this way, in the reads' immediate offsets, instead of moving the offsets per tile)
+      auto sd_load = [&](int blk, int buf = 0) {
+        return [&, blk, buf](int i) {
+          const int ka = 32 * blk * KRB + buf * K_TILE, va = 32 * blk * VRB + buf * V_TILE;
           Frag a;
-          if (i < NC) a.u = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(koff[i] + 32 * blk * KRB);
-          else if (kSameRows) a.u = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(koff[i - NC] + 2 * K_TILE + 32 * blk * VRB);
-          else a.u = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(vnoff[i - NC] + 32 * blk * VRB);
+          if (i < NC) a.u = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(koff[i] + ka);
+          else if (kSameRows) a.u = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(koff[i - NC] + (2 * K_TILE + va));
+          else a.u = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(vnoff[i - NC] + va);
           return a;
         };
       };
@@ -214,8 +217,8 @@ __global__ __launch_bounds__(kThreads, DQK <= 128 ? 2 : 1) void bwd_dq_kernel(co
           }
         };
       };
-      auto gr_frag = [&](int blk, int j, int db) {
-        const uint32_t base = (32 * blk + 16 * j) * KRB;
+      auto gr_frag = [&](int blk, int j, int db, int buf = 0) {
+        const uint32_t base = (32 * blk + 16 * j) * KRB + buf * K_TILE;
         Frag a;
         a.h[0] = lds_read_tr16_at(ktoff[0][db] + base);
         a.h[1] = lds_read_tr16_at(ktoff[1][db] + base);
@@ -254,32 +257,34 @@ __global__ __launch_bounds__(kThreads, DQK <= 128 ? 2 : 1) void bwd_dq_kernel(co
           for (int db = 0; db < NDB; ++db) ktoff[r][db] += dk;
         cur_buf = buf;
       };
-      auto begin_tile = [&](int kt) {
+      auto begin_tile = [&](int kt, bool point = true) {
         race_fence();
         wait_async_loads();
         __syncthreads();
         if (kt + 1 < nkt) issue(kt + 1);
-        if ((kt & 1) != cur_buf) point_offsets_at(kt & 1);
+        if (point && (kt & 1) != cur_buf) point_offsets_at(kt & 1);
       };
 
       const int n_interior = wave_active ? min(nkt, (qw0 + 1) / BN) : 0;
-      int kt = 0;
-      for (; kt < n_interior; ++kt) {
-        begin_tile(kt);
+      // One interior tile.  BUF = kt & 1 as a compile-time constant: the lane's offsets stay on buffer 0
+      // and the reads carry the buffer in their immediate offsets; BUF < 0: the offsets follow the buffers.
+      auto interior_tile = [&](auto bufc, int kt) {
+        constexpr int BUF = decltype(bufc)::value < 0 ? 0 : decltype(bufc)::value;
+        begin_tile(kt, decltype(bufc)::value < 0);
         const int k_off = kt * BN;
         Blk x0, x1;
         LdsChain<NC + NCV, PD> c1;
-        c1.prefill(sd_load(0));
-        c1.run(sd_load(0), sd_mma(x0));
-        c1.prefill(sd_load(1));
+        c1.prefill(sd_load(0, BUF));
+        c1.run(sd_load(0, BUF), sd_mma(x0));
+        c1.prefill(sd_load(1, BUF));
         if (kVgprScores) mfma_results_ready(x0.s, x0.dp);
-        c1.template run_with<17>(sd_load(1), sd_mma(x1), [&](int k) { sm_slice(x0, k_off, k, std::false_type{}); });
+        c1.template run_with<17>(sd_load(1, BUF), sd_mma(x1), [&](int k) { sm_slice(x0, k_off, k, std::false_type{}); });
         // gr(0) (2*NDB MFMAs) then gr(1) j=0 (NDB) then gr(1) j=1 (NDB), with sm(1) spread so that
         // dS chunk j of block 1 is complete before the MFMAs that read it
         constexpr int LG = 4 * NDB;
         auto g_load = [&](int i) {
           const int blk = i / (2 * NDB), j = (i / NDB) & 1, db = i % NDB;
-          return gr_frag(blk, j, db);
+          return gr_frag(blk, j, db, BUF);
         };
         LdsChain<LG, PD> c2;
         c2.prefill(g_load);
@@ -302,7 +307,13 @@ __global__ __launch_bounds__(kThreads, DQK <= 128 ? 2 : 1) void bwd_dq_kernel(co
           }
           __builtin_amdgcn_sched_barrier(0);
         }
+      };
+      int kt = 0;  // the offsets point at buffer 0 here
+      for (; kt + 1 < n_interior; kt += 2) {
+        interior_tile(std::integral_constant<int, 0>{}, kt);
+        interior_tile(std::integral_constant<int, 1>{}, kt + 1);
       }
+      for (; kt < n_interior; ++kt) interior_tile(std::integral_constant<int, -1>{}, kt);
       for (; kt < nkt; ++kt) {  // tiles that touch the diagonal: plain masked path, block by block
         begin_tile(kt);
         const int k_off = kt * BN;
