@@ -461,8 +461,7 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
       int skip = w_share >= 8 && ((tl.tile / w_share) & 1) ? (tl.tile % w_share) * (BN / BQ) : 0;
       skip = max(0, min(skip, nqb - 1));
       const int first_blk = nqb - 1 - skip;
-      // block of the sb-th group of g steps: first_blk .. 0, then nqb-1 .. first_blk+1
-      auto block_of = [&](int sb) { return sb <= first_blk ? first_blk - sb : nqb + first_blk - sb; };
+      // the blocks are taken in the order first_blk .. 0, then nqb-1 .. first_blk+1, g steps each
       // Copies are issued in step order; the source pointers of the next block to copy are carried
       // along instead of being recomputed from the step number.
       const int64_t first_row = (int64_t)s0 + qb_start + (int64_t)first_blk * BQ;
@@ -473,32 +472,52 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
       const uint16_t* o_src = o_blk;
       const float* row_src = row_blk;
       int blk_next = first_blk, head_next = 0;
-      auto issue_next = [&](int buf) {
-        const int valid = s_len - qb_start - blk_next * BQ;  // >= 1; < BQ only for the sample's last block
-        q_loader.issue(q_src, q_stride_b, valid, q_lds + buf * Q_TILE, wave, lane);
-        o_loader.issue(o_src, o_stride_b, valid, o_lds + buf * O_TILE, wave, lane);
-        if (wave < 2) {
-          // issued through the same untracked path as the tiles: the compiler must not see an LDS
-          // write here, or it would drain every outstanding copy before the next LDS read
-          const int row = lane < valid ? lane : valid - 1;
-          const float* dst = (wave == 0 ? lse_lds : d_lds) + buf * BQ;
-          async_copy4(row_src, (uint32_t)row * 4u, lds_address(dst));
-        }
-        if (++head_next == g_item) {  // on to the block before; from the tile's own block to the sample's last
-          head_next = 0;
-          const int64_t jump = blk_next == 0 ? (int64_t)(nqb - 1) * BQ : -(int64_t)BQ;
-          blk_next = blk_next == 0 ? nqb - 1 : blk_next - 1;
-          q_blk += jump * p.q_st;
-          o_blk += jump * p.o_st;
-          row_blk += jump;
-          q_src = q_blk;
-          o_src = o_blk;
-          row_src = row_blk;
+      // The copies of a step's operands are issued one at a time (slot 0 .. N_COPY-1), so that they can sit
+      // behind the MFMAs of the step before; taking the last slot moves the source on to the next step.
+      // qb_in[buf]: first query row (in-sample) of the block whose copies went to buffer buf.
+      constexpr int NQC = decltype(q_loader)::PER_WAVE, NOC = decltype(o_loader)::PER_WAVE;
+      constexpr int N_COPY = NQC + NOC + 1;
+      int qb_in[2] = {0, 0};
+      // FULL: all BQ rows of the block exist (no clamping of the source rows, no vector arithmetic at all)
+      auto issue_copy = [&](int slot, int buf, auto full_tag) {
+        constexpr bool FULL = decltype(full_tag)::value;
+        const int valid = FULL ? BQ : s_len - qb_start - blk_next * BQ;  // >= 1; < BQ only for the sample's last block
+        if (slot < NQC) {
+          if (FULL) q_loader.issue_full(slot, q_src, q_lds + buf * Q_TILE, wave);
+          else q_loader.issue_one(slot, q_src, q_stride_b, valid, q_lds + buf * Q_TILE, wave, lane);
+        } else if (slot < NQC + NOC) {
+          if (FULL) o_loader.issue_full(slot - NQC, o_src, o_lds + buf * O_TILE, wave);
+          else o_loader.issue_one(slot - NQC, o_src, o_stride_b, valid, o_lds + buf * O_TILE, wave, lane);
         } else {
-          q_src += p.q_sh;
-          o_src += p.o_sh;
-          row_src += p.T;
+          if (wave < 2) {
+            // issued through the same untracked path as the tiles: the compiler must not see an LDS
+            // write here, or it would drain every outstanding copy before the next LDS read
+            const int row = lane < valid ? lane : valid - 1;
+            const float* dst = (wave == 0 ? lse_lds : d_lds) + buf * BQ;
+            async_copy4(row_src, (uint32_t)row * 4u, lds_address(dst));
+          }
+          qb_in[buf] = qb_start + blk_next * BQ;
+          if (++head_next == g_item) {  // on to the block before; from the tile's own block to the sample's last
+            head_next = 0;
+            const int64_t jump = blk_next == 0 ? (int64_t)(nqb - 1) * BQ : -(int64_t)BQ;
+            blk_next = blk_next == 0 ? nqb - 1 : blk_next - 1;
+            q_blk += jump * p.q_st;
+            o_blk += jump * p.o_st;
+            row_blk += jump;
+            q_src = q_blk;
+            o_src = o_blk;
+            row_src = row_blk;
+          } else {
+            q_src += p.q_sh;
+            o_src += p.o_sh;
+            row_src += p.T;
+          }
         }
+      };
+      auto next_is_full = [&]() { return s_len - qb_start - blk_next * BQ >= BQ; };
+      auto issue_next = [&](int buf) {  // all of a step's copies in one go
+#pragma unroll
+        for (int slot = 0; slot < N_COPY; ++slot) issue_copy(slot, buf, std::false_type{});
       };
       if (n_steps > 0) issue_next(0);
 
@@ -535,11 +554,13 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
         Frag pb[2], dsb[2];
       };
       constexpr int kPD = 3;  // LDS read-ahead depth (fragments)
-      auto do_step = [&](int step, auto buf_tag) {
+      // active: a step of the item (not the idle one that makes the count even); has_next: another step
+      // follows, whose operands this step copies into the other buffer.
+      auto do_step = [&](auto buf_tag, bool active, bool has_next) {
         // the step's buffer is a compile-time constant: it goes into the immediate offset of every LDS
         // read (two copies of the step's code instead of 34 address updates per step)
         constexpr int BUF = decltype(buf_tag)::value;
-        const int qb = qb_start + block_of(step / g_item) * BQ;
+        const int qb = qb_in[BUF];
         auto sd_load = [&](int sub) {
           return [&, sub](int i) {
             Frag a;
@@ -654,18 +675,33 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
         // chains at the end), whatever path computed the probabilities: with updates in several
         // branches the compiler keeps a second set of the 128 accumulator registers and copies one
         // set to the other in every step (one vector instruction per register).
-        // else: block lies above this wave's keys, or this is the idle step that makes the count even
-        const bool in_reach = wave_active && step < n_steps && qb + BQ - 1 >= kw0_in;
+        //
+        // The step opens with the first LDS reads of sub-block A, which depend on nothing but the buffer: a
+        // single wave per SIMD has nothing else to run while they are under way, so everything that can wait
+        // (the step's flags, the copies for the next step) comes after them, and the copies go out one by one
+        // behind the first MFMA chain, which carries no vector arithmetic (measured per step of 3600 clocks:
+        // 800 clocks from the last MFMA of a step to the first of the next with the bookkeeping, a burst of
+        // copies and the reads one after the other; 350 this way, and the copies cost the chain 340).
+        Sub xa, xb;
+        LdsChain<NC + NCV, kPD> c1;
+        c1.prefill(sd_load(0));
+        init_dp(xa, 0);  // behind the operand reads: only the first dP MFMA needs it
+        // not in reach: the block lies above this wave's keys, or this is the idle step that makes the count even
+        const bool in_reach = wave_active && active && qb + BQ - 1 >= kw0_in;
         const bool need_a = in_reach && qb + 31 >= kw0_in;           // qb < s_len always holds
         const bool need_b = in_reach && qb + 63 >= kw0_in && qb + 32 < s_len;
         const bool any_mask = kw0_in + 31 > qb || qb + 63 >= s_len;  // diagonal or sample tail in reach
         const bool pair = need_a && need_b && !any_mask;
-        Sub xa, xb;
         if (pair) {
-          LdsChain<NC + NCV, kPD> c1;
-          init_dp(xa, 0);
-          c1.prefill(sd_load(0));
-          c1.run(sd_load(0), sd_mma(xa));
+          // a next block with all its rows (every block but a sample's last) is copied slot by slot behind
+          // the MFMAs; the clamped form needs vector arithmetic and registers, and goes out up front.  One
+          // chain for both cases: with the chain on two paths the compiler joins the score registers by
+          // copies placed right behind the asm MFMAs, before their results exist.
+          const bool behind = has_next && next_is_full();
+          if (has_next && !behind) issue_next(1 - BUF);
+          c1.template run_with<N_COPY>(sd_load(0), sd_mma(xa), [&](int slot) {
+            if (behind) issue_copy(slot, 1 - BUF, std::true_type{});
+          });
           rows_prefetch(0, 0);
           init_dp(xb, 1);
           c1.prefill(sd_load(1));
@@ -676,10 +712,8 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
           // sub-block A: masked, finished here.  Sub-block B: its probabilities are formed by the same
           // unmasked slices as on the fast path (behind the first gr chain below), so the mask goes
           // into the scores instead: -inf gives exp2 = 0 (the scale is positive) and dS = 0 (dP - D).
+          if (has_next) issue_next(1 - BUF);
           if (need_a) {
-            LdsChain<NC + NCV, kPD> c1;
-            init_dp(xa, 0);
-            c1.prefill(sd_load(0));
             c1.run(sd_load(0), sd_mma(xa));
             rows_prefetch(0, 0);
             if (kVgprScores) mfma_results_ready(xa.s, xa.dp);
@@ -693,7 +727,6 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
             }
           }
           if (need_b) {
-            LdsChain<NC + NCV, kPD> c1;
             init_dp(xb, 1);
             c1.prefill(sd_load(1));
             c1.run(sd_load(1), sd_mma(xb));
@@ -728,13 +761,11 @@ __global__ __launch_bounds__(kThreads, 1) void bwd_dkdv_kernel(const BwdParams p
       for (int step = 0; step < n_steps; step += 2) {
         wait_async_loads();
         __syncthreads();
-        if (step + 1 < n_steps) issue_next(1);
-        do_step(step, std::integral_constant<int, 0>{});
+        do_step(std::integral_constant<int, 0>{}, true, step + 1 < n_steps);
         race_fence();
         wait_async_loads();
         __syncthreads();
-        if (step + 2 < n_steps) issue_next(0);
-        do_step(step + 1, std::integral_constant<int, 1>{});
+        do_step(std::integral_constant<int, 1>{}, step + 1 < n_steps, step + 2 < n_steps);
         race_fence();
       }
 
