@@ -138,14 +138,22 @@ __global__ __launch_bounds__(kThreads, DQK <= 128 ? 2 : 1) void bwd_dq_kernel(co
       const uint16_t* kbase = p.k + (int64_t)s0 * p.k_st + (int64_t)kh * p.k_sh;
       const uint16_t* vbase = p.v + (int64_t)s0 * p.v_st + (int64_t)kh * p.v_sh;
 
-      auto issue = [&](int kt) {
+      // copy `slot` of this wave's share of key tile kt (K first, then V)
+      constexpr int NKCP = decltype(k_loader)::PER_WAVE, NVCP = decltype(v_loader)::PER_WAVE;
+      auto issue_slot = [&](int kt, int slot) {
         const int k_off = kt * BN;
         const int valid = n_keys - k_off;
-        k_loader.issue(kbase + (int64_t)k_off * p.k_st, k_stride_b, valid, k_lds + (kt & 1) * K_TILE, wave);
-        if constexpr (kSameRows)
-          k_loader.issue(vbase + (int64_t)k_off * p.v_st, v_stride_b, valid, v_lds + (kt & 1) * V_TILE, wave);
-        else
-          v_loader.issue(vbase + (int64_t)k_off * p.v_st, v_stride_b, valid, v_lds + (kt & 1) * V_TILE, wave);
+        if (slot < NKCP) {
+          k_loader.issue_one(slot, kbase + (int64_t)k_off * p.k_st, k_stride_b, valid, k_lds + (kt & 1) * K_TILE, wave);
+        } else if constexpr (kSameRows) {
+          k_loader.issue_one(slot - NKCP, vbase + (int64_t)k_off * p.v_st, v_stride_b, valid, v_lds + (kt & 1) * V_TILE, wave);
+        } else {
+          v_loader.issue_one(slot - NKCP, vbase + (int64_t)k_off * p.v_st, v_stride_b, valid, v_lds + (kt & 1) * V_TILE, wave);
+        }
+      };
+      auto issue = [&](int kt) {
+#pragma unroll
+        for (int slot = 0; slot < NKCP + NVCP; ++slot) issue_slot(kt, slot);
       };
       issue(0);
 
@@ -257,11 +265,13 @@ __global__ __launch_bounds__(kThreads, DQK <= 128 ? 2 : 1) void bwd_dq_kernel(co
           for (int db = 0; db < NDB; ++db) ktoff[r][db] += dk;
         cur_buf = buf;
       };
-      auto begin_tile = [&](int kt, bool point = true) {
+      // copies_now: the next tile's copies go out here in one go; an interior tile spreads them behind the MFMAs
+      // of its first chain instead (a tile follows every interior tile)
+      auto begin_tile = [&](int kt, bool point = true, bool copies_now = true) {
         race_fence();
         wait_async_loads();
         __syncthreads();
-        if (kt + 1 < nkt) issue(kt + 1);
+        if (copies_now && kt + 1 < nkt) issue(kt + 1);
         if (point && (kt & 1) != cur_buf) point_offsets_at(kt & 1);
       };
 
@@ -270,12 +280,12 @@ __global__ __launch_bounds__(kThreads, DQK <= 128 ? 2 : 1) void bwd_dq_kernel(co
       // and the reads carry the buffer in their immediate offsets; BUF < 0: the offsets follow the buffers.
       auto interior_tile = [&](auto bufc, int kt) {
         constexpr int BUF = decltype(bufc)::value < 0 ? 0 : decltype(bufc)::value;
-        begin_tile(kt, decltype(bufc)::value < 0);
+        begin_tile(kt, decltype(bufc)::value < 0, false);
         const int k_off = kt * BN;
         Blk x0, x1;
         LdsChain<NC + NCV, PD> c1;
         c1.prefill(sd_load(0, BUF));
-        c1.run(sd_load(0, BUF), sd_mma(x0));
+        c1.template run_with<NKCP + NVCP>(sd_load(0, BUF), sd_mma(x0), [&](int slot) { issue_slot(kt + 1, slot); });
         c1.prefill(sd_load(1, BUF));
         if (kVgprScores) mfma_results_ready(x0.s, x0.dp);
         c1.template run_with<17>(sd_load(1, BUF), sd_mma(x1), [&](int k) { sm_slice(x0, k_off, k, std::false_type{}); });
