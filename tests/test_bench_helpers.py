@@ -35,3 +35,12 @@ def test_more_than_one_gpu_is_refused_with_a_message():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], stdout=subprocess.PIPE,
                        stderr=subprocess.PIPE, text=True, timeout=120)
     assert r.returncode == 2 and "ONE GPU" in r.stderr
+
+
+def test_the_traffic_table_has_a_row_for_the_kernel_sources_as_they_stand():
+    """roofline.traffic of the default bench line comes from counter runs on a particular build of the dominant
+    kernel; a change to its sources without new counter runs would silently turn the figure into null."""
+    import bench
+    assert bench.measured_traffic_bytes(3, 0) is not None, (
+        "profiles/hbm_traffic_table.md has no row for workload 3, seed 0 and kernel sources digest %s: "
+        "run the FETCH_SIZE and WRITE_SIZE counter passes again and add the row" % bench.kernel_sources_digest())
